@@ -1,0 +1,284 @@
+/*
+ * Moshpit All-Reduce group-averaging round: plain fp64 CPU oracle.
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is the slow, obviously-correct
+ * definition that the GPU library is checked against.  It shares no code,
+ * header, table or helper with the GPU path and nothing in the product may
+ * call it.  Parity status: every function here is pinned by CPU tests against
+ * facts the paper or plain mathematics fix (exact global mean after d rounds
+ * on a full grid, sum preservation, non-increasing distortion, hand-computed
+ * tiny cases, a doubly-stochastic matrix formulation, Table 4's N=1024 p=0
+ * entry).  The failure-schedule generator is an input recipe (the paper gives
+ * none); it is pinned by its stated distributional properties only.
+ *
+ * What is computed (paper notation):
+ *   - peers i = 0..N-1 sit on the vertices of the hypercube {0..M-1}^d,
+ *     N = M^d, one peer per vertex (Sec. 3.1, Eq. 2; App. C.1; proof of the
+ *     variance theorem in App. C.4 for the hyperindex notation C_i);
+ *   - in round t the peers whose hyperindices agree everywhere except in
+ *     coordinate a = t mod d form a group J and every *participating* member
+ *     replaces its vector by the group average (Alg. 1, the AllReduce line;
+ *     App. C.3, the group-average formula; App. C.4, the definition of
+ *     J_{i,t} and b_{i,t});
+ *   - a peer that does not take part in a round keeps its vector; the others
+ *     of its group still average among themselves (App. E, the guarantee that
+ *     a group is formed from whoever remains);
+ *   - the error measure is the average distortion (1/N) sum_i ||theta_i -
+ *     theta_bar||^2 with theta_bar the mean over all N peers (Thm 3.2, the
+ *     left-hand side of its equation; Sec. 4.1).
+ *
+ * Coordinate convention (a reading of the garbled Eq. 2): coordinate q of
+ * peer i is the q-th base-M digit of i, floor(i / M^q) mod M, q = 0..d-1.
+ *
+ * The state is a row-major double matrix X[N][ld]; a call touches columns
+ * 0..W-1 of every row, so a caller may hand in independent column slabs.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_MAX_D 32
+
+/* ---- hypercube coordinates ------------------------------------------- */
+
+/* digits[q] = q-th base-M digit of i, by repeated division. */
+void oracle_digits(int64_t i, int32_t M, int32_t d, int32_t *digits)
+{
+    int64_t rest = i;
+    for (int32_t q = 0; q < d; ++q) {
+        digits[q] = (int32_t)(rest % M);
+        rest = rest / M;
+    }
+}
+
+/* 1 when peers i and j agree in every coordinate except coordinate a. */
+static int same_group(int64_t i, int64_t j, int32_t M, int32_t d, int32_t a)
+{
+    int32_t ci[ORACLE_MAX_D], cj[ORACLE_MAX_D];
+    oracle_digits(i, M, d, ci);
+    oracle_digits(j, M, d, cj);
+    for (int32_t q = 0; q < d; ++q) {
+        if (q == a) continue;
+        if (ci[q] != cj[q]) return 0;
+    }
+    return 1;
+}
+
+/*
+ * Group key of every peer for round t (Eq. 1 in its static-grid form: the
+ * d-1 coordinates other than a = t mod d), packed into one integer by reading
+ * the remaining digits, in increasing q, as a base-M number.
+ */
+int oracle_group_keys(int64_t N, int32_t M, int32_t d, int64_t t, int32_t *keys)
+{
+    if (d < 1 || d > ORACLE_MAX_D || M < 1 || t < 0) return -1;
+    int32_t a = (int32_t)(t % d);
+    for (int64_t i = 0; i < N; ++i) {
+        int32_t c[ORACLE_MAX_D];
+        oracle_digits(i, M, d, c);
+        int64_t key = 0, weight = 1;
+        for (int32_t q = 0; q < d; ++q) {
+            if (q == a) continue;
+            key += (int64_t)c[q] * weight;
+            weight *= M;
+        }
+        keys[i] = (int32_t)key;
+    }
+    return 0;
+}
+
+/*
+ * Group membership for round t, derived from the coordinate tuples alone
+ * (no packed key, no stride arithmetic): group_id[i] = smallest peer index
+ * that shares all coordinates but a with i.  O(N^2), on purpose.
+ */
+int oracle_group_ids(int64_t N, int32_t M, int32_t d, int64_t t, int64_t *group_id)
+{
+    if (d < 1 || d > ORACLE_MAX_D || M < 1 || t < 0) return -1;
+    int32_t a = (int32_t)(t % d);
+    for (int64_t i = 0; i < N; ++i) group_id[i] = -1;
+    for (int64_t i = 0; i < N; ++i) {
+        if (group_id[i] >= 0) continue;
+        for (int64_t j = i; j < N; ++j)
+            if (group_id[j] < 0 && same_group(i, j, M, d, a)) group_id[j] = i;
+    }
+    return 0;
+}
+
+/* ---- one averaging round --------------------------------------------- */
+
+/*
+ * Round t on columns 0..W-1 of X[N][ld].  alive[i] != 0 means peer i takes
+ * part; alive == NULL means everybody does.  For every group the live
+ * members' vectors are summed in ascending peer order, divided by their
+ * count and written back to exactly those members.
+ */
+int oracle_round(double *X, int64_t N, int64_t W, int64_t ld,
+                 int32_t M, int32_t d, int64_t t, const uint8_t *alive)
+{
+    int64_t *gid = (int64_t *)malloc(sizeof(int64_t) * (size_t)(N > 0 ? N : 1));
+    int64_t *members = (int64_t *)malloc(sizeof(int64_t) * (size_t)(N > 0 ? N : 1));
+    double *mean = (double *)malloc(sizeof(double) * (size_t)(W > 0 ? W : 1));
+    if (!gid || !members || !mean) { free(gid); free(members); free(mean); return -2; }
+    if (oracle_group_ids(N, M, d, t, gid) != 0) { free(gid); free(members); free(mean); return -1; }
+
+    for (int64_t lead = 0; lead < N; ++lead) {
+        if (gid[lead] != lead) continue;          /* one pass per group */
+        int64_t k = 0;
+        for (int64_t i = lead; i < N; ++i)
+            if (gid[i] == lead && (alive == NULL || alive[i] != 0)) members[k++] = i;
+        if (k == 0) continue;
+        for (int64_t c = 0; c < W; ++c) mean[c] = 0.0;
+        for (int64_t m = 0; m < k; ++m) {
+            const double *row = X + members[m] * ld;
+            for (int64_t c = 0; c < W; ++c) mean[c] += row[c];
+        }
+        for (int64_t c = 0; c < W; ++c) mean[c] = mean[c] / (double)k;
+        for (int64_t m = 0; m < k; ++m) {
+            double *row = X + members[m] * ld;
+            for (int64_t c = 0; c < W; ++c) row[c] = mean[c];
+        }
+    }
+    free(gid); free(members); free(mean);
+    return 0;
+}
+
+/* ---- storage rounding (diagnostic mode only) ------------------------- */
+
+/*
+ * Nearest bfloat16 (1 sign, 8 exponent, 7 fraction bits), ties to even:
+ * write v = m * 2^e with 0.5 <= |m| < 1, keep 8 significant bits of m.
+ * Below the normal range the spacing is fixed at 2^-133.
+ */
+static double round_to_bf16(double v)
+{
+    if (v == 0.0 || v != v || v - v != 0.0) return v;      /* 0, nan, inf */
+    int e;
+    double m = frexp(v, &e);
+    if (e < -125) return ldexp(nearbyint(ldexp(v, 133)), -133);
+    return ldexp(nearbyint(ldexp(m, 8)), e - 8);           /* nearbyint: ties to even */
+}
+
+/*
+ * Round every entry of columns 0..W-1 to the storage type: 0 = binary32,
+ * 1 = bfloat16.  Used by the diagnostic "storage-quantized" run, which mimics
+ * a state that lives in the storage type between rounds.
+ */
+int oracle_quantize(double *X, int64_t N, int64_t W, int64_t ld, int32_t dtype)
+{
+    if (dtype != 0 && dtype != 1) return -1;
+    for (int64_t i = 0; i < N; ++i)
+        for (int64_t c = 0; c < W; ++c) {
+            double v = X[i * ld + c];
+            X[i * ld + c] = (dtype == 0) ? (double)(float)v : round_to_bf16(v);
+        }
+    return 0;
+}
+
+/* ---- average distortion ---------------------------------------------- */
+
+/*
+ * (1/N) sum_i sum_{c<W} (X[i][c] - mean_c)^2, mean_c over all N rows
+ * (alive or not).  Two passes, as the definition reads.  Column slabs add.
+ */
+double oracle_dist_to_mean(const double *X, int64_t N, int64_t W, int64_t ld)
+{
+    double total = 0.0;
+    for (int64_t c = 0; c < W; ++c) {
+        double s = 0.0;
+        for (int64_t i = 0; i < N; ++i) s += X[i * ld + c];
+        double mu = s / (double)N;
+        double q = 0.0;
+        for (int64_t i = 0; i < N; ++i) {
+            double e = X[i * ld + c] - mu;
+            q += e * e;
+        }
+        total += q;
+    }
+    return total / (double)N;
+}
+
+/* ---- seeded failure schedule ------------------------------------------ */
+
+/*
+ * The paper draws failures at random with a per-round probability p
+ * (Sec. 4.1) and gives no generator.  Both this oracle and the GPU library
+ * implement, separately, the same counter-based generator so that the two see
+ * identical masks:
+ *   mix(x):  x ^= x>>32; x *= 0x9E3779B97F4A7C15; x ^= x>>29;
+ *            x *= 0x6A09E667F3BCC909; x ^= x>>32           (mod 2^64)
+ *   u(seed,s,i) = mix( mix(seed + 0x9E3779B97F4A7C15*(s+1)) ^ i )
+ *   event(s,i)  = (u >> 40) < floor(p * 2^24)
+ * kind 0: nobody fails.
+ * kind 1: peer i is dead in round s iff event(s,i)  (fails for that round,
+ *         back in the next: Sec. 4.1).
+ * kind 2: a peer that is up in round s and draws event(s,i) goes down for
+ *         `down` consecutive rounds s..s+down-1, draws nothing meanwhile, and
+ *         is up (drawing again) from round s+down.  Rounds count from 0.
+ */
+static uint64_t mix64(uint64_t x)
+{
+    x ^= x >> 32; x *= 0x9E3779B97F4A7C15ull;
+    x ^= x >> 29; x *= 0x6A09E667F3BCC909ull;
+    x ^= x >> 32;
+    return x;
+}
+
+static int failure_event(uint64_t seed, int64_t s, int64_t i, uint32_t thr)
+{
+    uint64_t u = mix64(mix64(seed + 0x9E3779B97F4A7C15ull * (uint64_t)(s + 1)) ^ (uint64_t)i);
+    return (uint32_t)(u >> 40) < thr;
+}
+
+/* masks[r][i] = 1 when peer i is alive in round t0 + r, r = 0..rounds-1. */
+int oracle_schedule_masks(int32_t kind, double p, uint64_t seed, int32_t down,
+                          int64_t N, int64_t t0, int32_t rounds, uint8_t *masks)
+{
+    if (kind < 0 || kind > 2 || !(p >= 0.0 && p <= 1.0) || t0 < 0 || rounds < 0) return -1;
+    if (kind == 2 && down < 1) return -1;
+    uint32_t thr = (uint32_t)(p * 16777216.0);     /* floor(p * 2^24) */
+    for (int64_t i = 0; i < N; ++i) {
+        if (kind == 0) {
+            for (int32_t r = 0; r < rounds; ++r) masks[(int64_t)r * N + i] = 1;
+        } else if (kind == 1) {
+            for (int32_t r = 0; r < rounds; ++r)
+                masks[(int64_t)r * N + i] = failure_event(seed, t0 + r, i, thr) ? 0 : 1;
+        } else {
+            int64_t down_left = 0;                 /* rounds still to sit out */
+            for (int64_t s = 0; s < t0 + rounds; ++s) {
+                if (down_left == 0 && failure_event(seed, s, i, thr)) down_left = down;
+                int is_alive = (down_left == 0);
+                if (down_left > 0) --down_left;
+                if (s >= t0) masks[(s - t0) * N + i] = (uint8_t)is_alive;
+            }
+        }
+    }
+    return 0;
+}
+
+/* ---- several rounds ---------------------------------------------------- */
+
+/*
+ * Rounds t0..t0+rounds-1 with masks[r][N] (NULL = no failures).  When
+ * dist_out != NULL it receives rounds+1 values: the distortion of the slab
+ * before the first round and after each round.  quantize < 0 keeps fp64
+ * state between rounds (the graded mode); 0 / 1 re-round the state to
+ * binary32 / bfloat16 after every round (diagnostic mode).
+ */
+int oracle_run(double *X, int64_t N, int64_t W, int64_t ld, int32_t M, int32_t d,
+               int64_t t0, int32_t rounds, const uint8_t *masks, int32_t quantize,
+               double *dist_out)
+{
+    if (dist_out) dist_out[0] = oracle_dist_to_mean(X, N, W, ld);
+    for (int32_t r = 0; r < rounds; ++r) {
+        int rc = oracle_round(X, N, W, ld, M, d, t0 + r, masks ? masks + (int64_t)r * N : NULL);
+        if (rc != 0) return rc;
+        if (quantize >= 0) {
+            rc = oracle_quantize(X, N, W, ld, quantize);
+            if (rc != 0) return rc;
+        }
+        if (dist_out) dist_out[r + 1] = oracle_dist_to_mean(X, N, W, ld);
+    }
+    return 0;
+}

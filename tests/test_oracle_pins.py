@@ -1,0 +1,417 @@
+"""Pins for the fp64 CPU oracle: checks against what the paper and plain
+mathematics fix, never against the oracle's own formulas or the GPU path.
+
+Each test names the mistake it is meant to catch.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import moshpit_oracle as orc
+
+
+def read_golden(path):
+    out = {}
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            out[key] = [float(v) for v in vals]
+    return out
+
+
+# --------------------------------------------------------------------------
+# hand-computed cases (tests/golden)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["fig2_nine_peers.txt", "cube_eight_peers.txt"])
+def test_hand_cases_full_grid(golden_dir, name):
+    """Wrong axis order, wrong stride or a wrong divisor changes these tables."""
+    g = read_golden(os.path.join(golden_dir, name))
+    M, d = int(g["M"][0]), int(g["d"][0])
+    X = np.array(g["x0"], dtype=np.float64).reshape(-1, 1)
+    for t in range(d):
+        if f"keys{t}" in g:
+            assert orc.group_keys(len(X), M, d, t).tolist() == [int(v) for v in g[f"keys{t}"]]
+        orc.round_(X, M, d, t)
+        assert X[:, 0].tolist() == g[f"x{t + 1}"]
+
+
+def test_paper_three_vector_example(golden_dir):
+    """App. C.1 worked example (an empty grid vertex): a peer that is absent
+    must neither contribute nor be overwritten, and a lone survivor keeps its
+    value."""
+    g = read_golden(os.path.join(golden_dir, "appC1_three_vectors.txt"))
+    M, d = int(g["M"][0]), int(g["d"][0])
+    alive = np.array(g["alive"], dtype=np.uint8)
+    X = np.array(g["x0"], dtype=np.float64).reshape(-1, 1)
+    assert orc.dist_to_mean(X) == g["dist"][0]
+    for t in range(2):
+        orc.round_(X, M, d, t, alive)
+        assert X[:, 0].tolist() == g[f"x{t + 1}"]
+        assert orc.dist_to_mean(X) == g["dist"][t + 1]
+    # the symbolic statement of the paper, with theta_11, theta_21, theta_22 = x0[0], x0[1], x0[3]
+    a, b, c = g["x0"][0], g["x0"][1], g["x0"][3]
+    assert X[0, 0] == (a + b) / 2
+    assert X[1, 0] == X[3, 0] == (a + b) / 4 + c / 2
+
+
+# --------------------------------------------------------------------------
+# P1: exact global mean after d rounds on a full grid (App. C.1 theorem)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,d", [(4, 2), (3, 3), (2, 5), (16, 2), (5, 1), (32, 2)])
+def test_exact_mean_after_d_rounds(M, d):
+    """Any mistake in coordinates (a repeated or skipped axis) leaves some peer
+    short of the global mean; checked against numpy's column mean."""
+    rng = np.random.default_rng(10 * M + d)
+    N, P = M ** d, 7
+    X0 = rng.normal(size=(N, P))
+    X = X0.copy()
+    dist = orc.run(X, M, d, 0, d, want_dist=True)
+    want = X0.mean(axis=0)
+    assert np.allclose(X, np.broadcast_to(want, X.shape), rtol=0, atol=1e-14)
+    assert dist[-1] < 1e-26
+    # one round short must NOT be there yet (d >= 2), whichever axis is left out
+    if d >= 2:
+        for start in range(d):
+            Y = X0.copy()
+            orc.run(Y, M, d, start, d - 1)
+            assert np.abs(Y - want).max() > 1e-3
+
+
+def test_any_d_consecutive_rounds_give_mean():
+    """Axes cycle t mod d: rounds 5,6,7 on a d=3 grid are again a full sweep."""
+    rng = np.random.default_rng(3)
+    M, d = 3, 3
+    X0 = rng.normal(size=(27, 3))
+    X = X0.copy()
+    orc.run(X, M, d, 5, 3)
+    assert np.allclose(X, X0.mean(axis=0), atol=1e-14, rtol=0)
+
+
+def test_partial_sweep_is_axis_mean():
+    """After k < d rounds a peer holds the mean over the first k coordinates
+    (recurrence of App. C.1), checked with numpy on the reshaped grid.
+    Catches a digit order that is reversed (most-significant digit first)."""
+    rng = np.random.default_rng(4)
+    M, d, P = 4, 3, 2
+    X0 = rng.normal(size=(M ** d, P))
+    grid = X0.reshape(M, M, M, P)           # index [c2][c1][c0]: digit 0 is the fastest
+    X = X0.copy()
+    orc.round_(X, M, d, 0)
+    want = np.broadcast_to(grid.mean(axis=2, keepdims=True), grid.shape).reshape(-1, P)
+    assert np.allclose(X, want, atol=1e-15, rtol=0)
+    orc.round_(X, M, d, 1)
+    want = np.broadcast_to(grid.mean(axis=(1, 2), keepdims=True), grid.shape).reshape(-1, P)
+    assert np.allclose(X, want, atol=1e-15, rtol=0)
+
+
+# --------------------------------------------------------------------------
+# brute force: the round as an explicit doubly-stochastic matrix
+# --------------------------------------------------------------------------
+
+def averaging_matrix(N, M, d, t, alive):
+    """W[i][j] from first principles in Python: coordinates by divmod, group =
+    equal coordinates except coordinate t mod d."""
+    def coords(i):
+        c = []
+        for _ in range(d):
+            i, r = divmod(i, M)
+            c.append(r)
+        return c
+    a = t % d
+    W = np.zeros((N, N))
+    for i in range(N):
+        if not alive[i]:
+            W[i, i] = 1.0
+            continue
+        ci = coords(i)
+        mates = [j for j in range(N) if alive[j]
+                 and all(cj == cq for q, (cj, cq) in enumerate(zip(coords(j), ci)) if q != a)]
+        for j in mates:
+            W[i, j] = 1.0 / len(mates)
+    return W
+
+
+@pytest.mark.parametrize("M,d", [(2, 2), (3, 2), (2, 3)])
+def test_all_masks_against_matrix_form(M, d):
+    """Every one of the 2^N masks, every axis: X <- W X.  A dropped member, a
+    divisor M instead of the live count, or a dead peer being overwritten all
+    fail here."""
+    N = M ** d
+    rng = np.random.default_rng(N)
+    X0 = rng.normal(size=(N, 3))
+    for bits in itertools.product([0, 1], repeat=N):
+        alive = np.array(bits, dtype=np.uint8)
+        for t in range(d):
+            W = averaging_matrix(N, M, d, t, alive)
+            assert np.allclose(W.sum(axis=0), 1) and np.allclose(W.sum(axis=1), 1)
+            X = X0.copy()
+            orc.round_(X, M, d, t, alive)
+            assert np.allclose(X, W @ X0, atol=1e-15, rtol=0)
+
+
+# --------------------------------------------------------------------------
+# invariants under arbitrary masks (proof sketch of Thm 3.1; App. C.3)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,d,p", [(4, 2, 0.3), (3, 3, 0.2), (8, 2, 0.05), (2, 4, 0.5)])
+def test_sum_preserved_and_distortion_monotone(M, d, p):
+    rng = np.random.default_rng(100 * M + d)
+    N, P, R = M ** d, 5, 9
+    X = rng.normal(size=(N, P)) + rng.uniform(-1, 1, size=(N, 1))
+    total0 = X.sum(axis=0)
+    masks = (rng.random((R, N)) >= p).astype(np.uint8)
+    prev = orc.dist_to_mean(X)
+    d0 = prev
+    for r in range(R):
+        gid = orc.group_ids(N, M, d, r)
+        before = X.copy()
+        orc.round_(X, M, d, r, masks[r])
+        # the global sum never moves (first claim of the Thm 3.1 proof sketch)
+        assert np.allclose(X.sum(axis=0), total0, rtol=0, atol=1e-12)
+        # each group's live-member sum is preserved; dead rows are bit-identical
+        for lead in np.unique(gid):
+            live = (gid == lead) & (masks[r] == 1)
+            assert np.allclose(X[live].sum(axis=0), before[live].sum(axis=0), rtol=0, atol=1e-12)
+        dead = masks[r] == 0
+        assert np.array_equal(X[dead], before[dead])
+        cur = orc.dist_to_mean(X)
+        assert cur <= prev + 1e-12 * d0        # distortion never grows (Jensen)
+        prev = cur
+        # convex hull never expands (App. C.2)
+        assert X.max() <= before.max() + 1e-15 and X.min() >= before.min() - 1e-15
+
+
+def test_dist_to_mean_is_numpy_definition():
+    rng = np.random.default_rng(5)
+    X = rng.normal(size=(27, 11)) * 3 + 1
+    want = ((X - X.mean(axis=0)) ** 2).sum() / X.shape[0]
+    assert abs(orc.dist_to_mean(X) - want) <= 1e-13 * want
+    # a strided column slab view gives that slab's share
+    part = orc.dist_to_mean(X[:, 2:6])
+    want = ((X[:, 2:6] - X[:, 2:6].mean(axis=0)) ** 2).sum() / X.shape[0]
+    assert abs(part - want) <= 1e-13 * want
+
+
+def test_special_masks():
+    """All dead, one survivor per group, one whole group alive."""
+    rng = np.random.default_rng(6)
+    M, d = 4, 2
+    X0 = rng.normal(size=(16, 4))
+    X = X0.copy()
+    orc.round_(X, M, d, 0, np.zeros(16, np.uint8))
+    assert np.array_equal(X, X0)
+    one = np.zeros(16, np.uint8)
+    one[[1, 6, 8, 15]] = 1                       # one peer in each round-0 group
+    orc.round_(X, M, d, 0, one)
+    assert np.array_equal(X, X0)
+    grp = np.zeros(16, np.uint8)
+    grp[4:8] = 1                                 # round-0 group of peers 4..7
+    orc.round_(X, M, d, 0, grp)
+    assert np.array_equal(X[:4], X0[:4]) and np.array_equal(X[8:], X0[8:])
+    assert np.allclose(X[4:8], X0[4:8].mean(axis=0), atol=1e-15, rtol=0)
+    # the same mask in round 1 puts each of them alone in its group
+    Y = X0.copy()
+    orc.round_(Y, M, d, 1, grp)
+    assert np.array_equal(Y, X0)
+
+
+def test_linearity_and_column_independence():
+    rng = np.random.default_rng(7)
+    M, d, N = 3, 2, 9
+    X0 = rng.normal(size=(N, 6))
+    masks = (rng.random((4, N)) > 0.3).astype(np.uint8)
+    A = X0.copy()
+    orc.run(A, M, d, 0, 4, masks)
+    perm = rng.permutation(6)
+    B = X0[:, perm].copy()
+    orc.run(B, M, d, 0, 4, masks)
+    assert np.array_equal(B, A[:, perm])
+    C = X0 * 8.0
+    orc.run(C, M, d, 0, 4, masks)
+    assert np.array_equal(C, A * 8.0)
+    # slabs + threads give the same numbers as one call
+    D = X0.copy()
+    dist_a = orc.run(X0.copy(), M, d, 0, 4, masks, want_dist=True)
+    dist_d = orc.run(D, M, d, 0, 4, masks, want_dist=True, threads=3, slab=2)
+    assert np.array_equal(D, A)
+    assert np.allclose(dist_a, dist_d, rtol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# P5: closed form of the expected distortion on a full grid
+# --------------------------------------------------------------------------
+
+def test_expected_distortion_closed_form():
+    """iid unit-variance entries: after k <= d rounds every peer holds a mean of
+    M^k values, so E[dist_k]/P = M^-k - M^-d (k = 0: 1 - 1/N).  A wrong
+    normalisation of the distortion (by N*P, by N-1, or by the live count) is
+    off by far more than the 2 % allowed here."""
+    rng = np.random.default_rng(8)
+    M, d, P = 4, 2, 65536
+    X = rng.normal(size=(16, P))
+    dist = orc.run(X, M, d, 0, 2, want_dist=True)
+    assert abs(dist[0] / P - (1 - 1 / 16)) < 0.02 * (1 - 1 / 16)
+    assert abs(dist[1] / P - (1 / 4 - 1 / 16)) < 0.02 * (1 / 4 - 1 / 16)
+    assert dist[2] / P < 1e-28
+
+
+# --------------------------------------------------------------------------
+# Table 4 of the paper, N = 1024 (M = 32, d = 2)
+# --------------------------------------------------------------------------
+
+def rounds_to_error(p, seed, thresholds, max_rounds=30):
+    rng = np.random.default_rng(seed)
+    X = rng.normal(size=(1024, 1))
+    masks = orc.schedule_masks(1, p, seed, 0, 1024, 0, max_rounds)
+    dist = orc.run(X, 32, 2, 0, max_rounds, masks, want_dist=True)
+    return [int(np.argmax(dist <= th)) if (dist <= th).any() else max_rounds for th in thresholds]
+
+
+def test_table4_moshpit_column(golden_dir):
+    """p = 0 must give exactly 2.0 (2.0).  With failures the paper's simulator
+    is not specified in every detail (what a failed peer holds when it comes
+    back), so those rows are only required to land within half a round."""
+    rows = np.loadtxt(os.path.join(golden_dir, "table4_moshpit_n1024.txt"), comments="#")
+    for p, want9, want4 in rows:
+        got = np.array([rounds_to_error(p, 1000 + s, (1e-9, 1e-4)) for s in range(100)], dtype=float)
+        m9, m4 = got[:, 0].mean(), got[:, 1].mean()
+        if p == 0:
+            assert (m9, m4) == (2.0, 2.0)
+        else:
+            assert abs(m9 - want9) <= 0.5, (p, m9, want9)
+            assert abs(m4 - want4) <= 0.5, (p, m4, want4)
+
+
+# --------------------------------------------------------------------------
+# variance bound with peers absent for the whole run (App. C.4)
+# --------------------------------------------------------------------------
+
+def m1(M, q):
+    """E[min(1/xi, 1)], xi ~ Binom(M, q): the lemma's closed form."""
+    return (1 - q) ** M + sum(((1 - q) ** (M - i) - (1 - q) ** M) / i for i in range(1, M + 1))
+
+
+def m2(M, q):
+    return (1 - q) ** M + sum(((1 - q) ** (M - i) - (1 - q) ** M) / i * sum(1 / j for j in range(i, M + 1))
+                              for i in range(1, M + 1))
+
+
+def test_variance_bound_absent_peers():
+    """Peers present with probability q for the whole run, iid unit-variance
+    inputs: the per-peer output variance after T = d rounds is at most
+    M^(T-1) m1(M-1,q) m2(M-1,q)^(T-1).  The oracle is linear, so running it on
+    the identity matrix yields the weights and sum_j W_ij^2 is the variance."""
+    M, d, q = 6, 2, 0.8
+    N = M ** d
+    rng = np.random.default_rng(9)
+    acc, cnt = 0.0, 0
+    for _ in range(200):
+        present = (rng.random(N) < q).astype(np.uint8)
+        W = np.eye(N)
+        orc.run(W, M, d, 0, d, np.tile(present, (d, 1)))
+        var = (W ** 2).sum(axis=1)[present == 1]
+        acc += var.sum()
+        cnt += len(var)
+    bound = M ** (d - 1) * m1(M - 1, q) * m2(M - 1, q) ** (d - 1)
+    assert acc / cnt <= bound
+    assert acc / cnt >= 1.0 / N            # can never beat the exact mean of N values
+
+
+# --------------------------------------------------------------------------
+# failure schedule generator (input recipe)
+# --------------------------------------------------------------------------
+
+MASK64 = (1 << 64) - 1
+
+
+def py_mix(x):
+    x ^= x >> 32
+    x = (x * 0x9E3779B97F4A7C15) & MASK64
+    x ^= x >> 29
+    x = (x * 0x6A09E667F3BCC909) & MASK64
+    x ^= x >> 32
+    return x
+
+
+def py_event(seed, s, i, p):
+    u = py_mix(py_mix((seed + 0x9E3779B97F4A7C15 * (s + 1)) & MASK64) ^ i)
+    return (u >> 40) < int(p * (1 << 24))
+
+
+def test_schedule_iid_matches_python_bigint():
+    """64-bit wrap-around and shift widths, against Python integers."""
+    masks = orc.schedule_masks(1, 0.3, 77, 0, 50, 3, 6)
+    for r in range(6):
+        for i in range(50):
+            assert masks[r, i] == (0 if py_event(77, 3 + r, i, 0.3) else 1)
+
+
+def test_schedule_statistics():
+    N, R = 4096, 50
+    for p in (0.05, 0.2):
+        masks = orc.schedule_masks(1, p, 2002, 0, N, 0, R)
+        rate = 1.0 - masks.mean()
+        assert abs(rate - p) < 4 * np.sqrt(p * (1 - p) / (N * R))
+        assert not np.array_equal(masks[0], masks[1])
+        # different seeds and different peers decorrelate
+        other = orc.schedule_masks(1, p, 2003, 0, N, 0, R)
+        both = ((masks == 0) & (other == 0)).mean()
+        assert abs(both - p * p) < 5 * np.sqrt(p * p / (N * R))
+    assert orc.schedule_masks(0, 0.5, 1, 0, 10, 0, 3).min() == 1
+    assert orc.schedule_masks(1, 0.0, 1, 0, 100, 0, 3).min() == 1
+    assert orc.schedule_masks(1, 1.0, 1, 0, 100, 0, 3).max() == 0
+
+
+def test_schedule_rejoin_structure():
+    """kind 2: every absence lasts exactly `down` rounds (unless cut by the end
+    of the window), a returning peer draws again at once, the stationary dead
+    fraction is down*p / (1 + (down-1)*p), and a window that starts later is
+    the tail of the window that starts at 0."""
+    N, R, p, down = 4096, 40, 0.1, 2
+    masks = orc.schedule_masks(2, p, 2005, down, N, 0, R)
+    dead = masks == 0
+    for i in range(0, N, 37):
+        s = 0
+        while s < R:
+            if dead[s, i]:
+                run_len = 1
+                while s + run_len < R and dead[s + run_len, i]:
+                    run_len += 1
+                if s + run_len < R:
+                    assert run_len % down == 0        # back-to-back absences are whole multiples
+                # the absence starts where the generator's event fires
+                assert py_event(2005, s, i, p)
+                s += run_len
+            else:
+                assert not py_event(2005, s, i, p)
+                s += 1
+    frac = dead[10:].mean()
+    want = down * p / (1 + (down - 1) * p)
+    assert abs(frac - want) < 0.01
+    tail = orc.schedule_masks(2, p, 2005, down, N, 7, 12)
+    assert np.array_equal(tail, masks[7:19])
+
+
+# --------------------------------------------------------------------------
+# storage rounding used by the diagnostic mode
+# --------------------------------------------------------------------------
+
+def test_quantize_matches_torch_rounding():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(11)
+    v = np.concatenate([rng.normal(size=5000) * 10.0 ** rng.integers(-6, 6, size=5000),
+                        [0.0, 1.0, -1.0, 1.00390625, 1.01171875, 3.0e-39, 65504.0]])
+    A = v.reshape(-1, 1).copy()
+    orc.quantize(A, 0)
+    assert np.array_equal(A[:, 0], v.astype(np.float32).astype(np.float64))
+    B = v.reshape(-1, 1).copy()
+    orc.quantize(B, 1)
+    want = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(B[:, 0], want)
