@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the Moshpit group-averaging hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic peer-state matrix:
+device-side generation of the failure masks for the workload's rounds, one
+group-mean kernel per round (axis cycling t mod d), and one dist-to-mean
+reduction of the resulting state.  Consecutive steps continue the round counter
+and work on the evolving state (timing depends on masks and addresses, not on
+values).  The state is resident in HBM before the timed region starts.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak bandwidth, GB/s (1 GB = 1e9 B)
+METRIC = "peer-state averaging GB/s per round and % of MI355X HBM peak; rounds/sec"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def live_in_groups(masks: np.ndarray, M: int, d: int, t0: int) -> np.ndarray:
+    """L_t per round: peers that take part and whose group has >= 2 participants
+    (the rows a round reads once and writes once).  Pure bookkeeping on the
+    mask bytes; axis a = t mod d has row stride M^a."""
+    out = np.zeros(len(masks), dtype=np.int64)
+    N = masks.shape[1]
+    for r, row in enumerate(masks):
+        a = (t0 + r) % d
+        S = M ** a
+        grid = row.reshape(N // (S * M), M, S).astype(np.int64)   # [upper digits][digit a][lower digits]
+        k = grid.sum(axis=1)
+        out[r] = int(k[k >= 2].sum())
+    return out
+
+
+def read_traffic(path: str):
+    """HBM bytes per launch of the dominant kernel from a committed rocprofv3
+    --pmc summary (a line `traffic_bytes_per_launch: <number>`), or None."""
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default: the largest, 4)")
+    ap.add_argument("--cpu-cols", type=int, default=-1,
+                    help="columns of the state the CPU oracle is timed on (0 = skip, -1 = auto)")
+    ap.add_argument("--no-copy-probe", action="store_true")
+    ap.add_argument("--tuning", type=str, default="", help="cols,unroll,nontemporal override for sweeps")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all peers are virtual peers in one GPU's HBM); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2103_03239_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    w = inputs.CONFIGS[args.config]
+    s = w.elem_size
+    log(f"[bench] workload {w.name}: N={w.N} (M={w.M}, d={w.d}) P={w.P} "
+        f"{'f32' if w.dtype == 0 else 'bf16'} state {w.N * w.P * s / 2**30:.2f} GiB, {w.rounds} rounds/step")
+    t_gen = time.time()
+    X = inputs.make_state(w, dev)
+    torch.cuda.synchronize()
+    log(f"[bench] state generated in {time.time() - t_gen:.1f}s")
+
+    sched = binding.Schedule(kind=w.kind, p=w.p, seed=w.mask_seed, down_rounds=w.down)
+    m = binding.Moshpit(w.N, w.P, w.M, w.d, w.dtype)
+    m.bind_state(X)
+    if args.tuning:
+        c, u, nt = (int(v) for v in args.tuning.split(","))
+        m.set_tuning(c, u, nt)
+
+    total_steps = args.warmup + args.steps
+    all_masks = m.schedule_mask(sched, 0, total_steps * w.rounds)
+    L = live_in_groups(all_masks, w.M, w.d, 0)
+    round_bytes = 2.0 * s * w.P * L                      # algorithmic bytes of every round
+    dist_bytes = float(w.N) * w.P * s                    # the distortion reads the state once
+
+    # cpu baseline input: first columns of the INITIAL state (copied before the GPU changes it)
+    cpu_cols = args.cpu_cols
+    if cpu_cols < 0:
+        cpu_cols = min(w.P, max(1024, (2 ** 31) // w.N))   # ~2^31 doubles = 16 GiB of fp64 at most
+    X_cpu = X[:, :cpu_cols].to("cpu") if cpu_cols > 0 else None
+
+    def step(k: int):
+        _, ms = m.run(k * w.rounds, w.rounds, sched, want_times=True)
+        dist = m.dist_to_mean()
+        return ms, dist
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    round_ms = []
+    dists = []
+    t0 = time.perf_counter()
+    for k in range(args.warmup, total_steps):
+        ms, dist = step(k)
+        round_ms.append(ms)
+        dists.append(dist)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    round_ms = np.array(round_ms, dtype=np.float64)               # [steps, rounds]
+    timed_bytes = round_bytes[args.warmup * w.rounds:].reshape(args.steps, w.rounds)
+    step_bytes = float(timed_bytes.sum()) + args.steps * dist_bytes
+    value = step_bytes / elapsed / 1e9
+    ms_per_step = elapsed / args.steps * 1e3
+    k1_bytes_per_launch = float(timed_bytes.mean())
+    k1_ms_per_launch = float(round_ms.mean())
+    k1_gbps = k1_bytes_per_launch / (k1_ms_per_launch * 1e-3) / 1e9
+    per_axis = {}
+    for a in range(w.d):
+        sel = [(r % w.d) == a for r in range(w.rounds)]          # steps start at multiples of rounds
+        if (w.rounds % w.d) != 0:
+            sel = None
+        if sel is not None:
+            sel = np.array(sel)
+            per_axis[f"axis{a}_gbps"] = round(float(timed_bytes[:, sel].sum() / (round_ms[:, sel].sum() * 1e-3) / 1e9), 1)
+    log(f"[bench] {args.steps} steps in {elapsed:.3f}s; group-mean kernel {k1_gbps:.0f} GB/s "
+        f"({100 * k1_gbps / HBM_PEAK_GBPS:.1f}% of peak), step {value:.0f} GB/s; dist/P after last step "
+        f"{dists[-1] / w.P:.3e}")
+
+    copy_gbps = None
+    if not args.no_copy_probe:
+        nbytes = min(w.N * w.P * s, 8 * 2 ** 30)
+        nbytes -= nbytes % 16
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        stream = torch.cuda.current_stream(dev)
+        for _ in range(2):
+            binding.copy_probe(dst, src, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(5):
+            binding.copy_probe(dst, src, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        copy_gbps = 5 * 2.0 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+        log(f"[bench] plain copy kernel: {copy_gbps:.0f} GB/s (read+write)")
+
+    cpu = None
+    if X_cpu is not None:
+        from oracle import moshpit_oracle as orc
+        threads = min(16, os.cpu_count() or 1)
+        ref = X_cpu.to(torch.float64).numpy()
+        del X_cpu
+        masks0 = all_masks[: w.rounds]
+        slab = max(1, -(-cpu_cols // threads))
+        t1 = time.perf_counter()
+        orc.run(ref, w.M, w.d, 0, w.rounds, masks0, threads=threads, slab=slab)
+        cpu_s = time.perf_counter() - t1
+        cpu_bytes = float((2.0 * s * cpu_cols * L[: w.rounds]).sum())
+        cpu = {"value": round(cpu_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+               "sample": f"{w.rounds} rounds of {w.name} on the first {cpu_cols} of {w.P} columns "
+                         f"(all {w.N} peers, fp64), {cpu_s:.2f} s",
+               "rounds_per_s_full_width": round(w.rounds / cpu_s * cpu_cols / w.P, 4)}
+        log(f"[bench] cpu oracle: {cpu['value']} GB/s on {threads} threads ({cpu_s:.1f}s)")
+
+    traffic = read_traffic(os.path.join(ROOT, "profiles", f"group_mean_cfg{args.config}_traffic.txt"))
+    out = {
+        "metric": METRIC,
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.dtype == 0 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "N": w.N, "M": w.M, "d": w.d, "P": w.P, "rounds_per_step": w.rounds,
+                   "failure_kind": w.kind, "failure_p": w.p, "state_bytes": w.N * w.P * s,
+                   "step": "mask generation + rounds x group-mean + 1 dist-to-mean"},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "rounds_per_s": round(w.rounds * args.steps / elapsed, 2),
+        "group_mean_gbps": round(k1_gbps, 1),
+        "group_mean_ms_per_round": round(k1_ms_per_launch, 4),
+        "group_mean_rounds_per_s": round(1e3 / k1_ms_per_launch, 2),
+        **per_axis,
+        "copy_probe_gbps": None if copy_gbps is None else round(copy_gbps, 1),
+        "dist_to_mean_per_param": dists[-1] / w.P,
+        "roofline": {"bound": "hbm", "achieved": round(k1_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(k1_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "kernel": "group_mean_kernel", "bytes_per_launch": k1_bytes_per_launch,
+                     "ms_per_launch": round(k1_ms_per_launch, 5)},
+        "cpu_baseline": cpu,
+    }
+    m.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,167 @@
+/*
+ * moshpit.h - C ABI of libmoshpit: Moshpit All-Reduce group-averaging rounds
+ * for N virtual peers whose parameter vectors are the rows of one matrix in a
+ * single MI355X's HBM.  All kernels are hand-written HIP for gfx950.
+ *
+ * Model (paper: Sec. 3.1, Alg. 1, Eq. 1-2; App. C.1; App. C.4 for notation).
+ *   Peers i = 0..N-1 are the vertices of the grid {0..M-1}^d, N = M^d;
+ *   coordinate q of peer i is the q-th base-M digit of i.  Round t averages
+ *   along coordinate a = t mod d: peers that agree in every other coordinate
+ *   form a group (at most M members, row stride M^a), and every member that
+ *   takes part in the round replaces its vector by the mean over the members
+ *   that take part.  A peer that does not take part keeps its vector and is
+ *   neither read nor written.  Rounds are numbered from 0.
+ *
+ * State layout.  X is row-major [N][row_stride] in device memory, P <=
+ * row_stride valid elements per row, element type float (binary32) or
+ * bfloat16.  Sums are accumulated in binary32 and rounded once, to nearest
+ * even, when stored.  The caller owns X; the library never allocates, frees or
+ * copies it.
+ *
+ * Conventions.  Every function returns MOSHPIT_OK (0) or a negative
+ * MOSHPIT_E* code and never throws; moshpit_last_error() gives a message for
+ * the last failure on that handle.  "host" / "device" says where a pointer
+ * must live.  Calls on one handle must not overlap in time; different handles
+ * are independent.  Work is queued on the stream given to
+ * moshpit_bind_state(); unless stated otherwise a call returns without waiting
+ * for the GPU.
+ */
+#ifndef MOSHPIT_H
+#define MOSHPIT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moshpit_ctx moshpit_ctx;   /* opaque; created/destroyed by the library */
+
+enum { MOSHPIT_F32 = 0, MOSHPIT_BF16 = 1 };
+
+enum {
+    MOSHPIT_OK     = 0,
+    MOSHPIT_EINVAL = -1,   /* bad argument (shape, alignment, range, NULL)      */
+    MOSHPIT_ENOMEM = -2,   /* host or device allocation failed                  */
+    MOSHPIT_EHIP   = -3,   /* a HIP runtime call failed; see moshpit_last_error */
+    MOSHPIT_ESTATE = -4    /* no state bound yet                                */
+};
+
+/* Failure schedule of a multi-round run (Sec. 4.1: each peer fails in a round
+ * with probability p and comes back later).  The paper gives no generator; the
+ * library uses a counter-based one so a schedule is a pure function of
+ * (seed, round, peer):
+ *   mix(x): x ^= x>>32; x *= 0x9E3779B97F4A7C15; x ^= x>>29;
+ *           x *= 0x6A09E667F3BCC909; x ^= x>>32                  (mod 2^64)
+ *   event(s,i) = (mix(mix(seed + 0x9E3779B97F4A7C15*(s+1)) ^ i) >> 40)
+ *                < floor(p * 2^24)
+ * kind MOSHPIT_SCHED_NONE     nobody ever fails;
+ * kind MOSHPIT_SCHED_IID      peer i is absent in round s iff event(s,i);
+ * kind MOSHPIT_SCHED_REJOIN   a present peer for which event(s,i) fires is
+ *                             absent for rounds s..s+down_rounds-1, draws
+ *                             nothing meanwhile and is present again (with its
+ *                             stale vector, drawing again) from s+down_rounds;
+ *                             the recursion starts at round 0;
+ * kind MOSHPIT_SCHED_EXPLICIT masks are given by the caller. */
+enum {
+    MOSHPIT_SCHED_NONE = 0, MOSHPIT_SCHED_IID = 1,
+    MOSHPIT_SCHED_REJOIN = 2, MOSHPIT_SCHED_EXPLICIT = 3
+};
+
+typedef struct {
+    int32_t  kind;
+    int32_t  down_rounds;           /* kind REJOIN: >= 1                          */
+    double   p;                     /* failure probability in [0,1]               */
+    uint64_t seed;
+    const uint8_t *explicit_masks;  /* kind EXPLICIT: host, [rounds][N], 1=alive  */
+} moshpit_schedule;
+
+/* Flags of moshpit_run. */
+enum {
+    MOSHPIT_RUN_DEFAULT = 0
+};
+
+/* Create a handle for N = M^d peers with P parameters each.
+ * Requires 2 <= M <= 64, d >= 1, N == M^d, P >= 1, dtype F32 or BF16;
+ * otherwise MOSHPIT_EINVAL and *out = NULL.  Allocates only small device
+ * scratch (masks, keys, reduction partials) on the current HIP device. */
+int moshpit_create(int64_t N, int64_t P, int32_t M, int32_t d, int32_t dtype, moshpit_ctx **out);
+
+/* Free the handle and its scratch (waits for the bound stream first). */
+int moshpit_destroy(moshpit_ctx *h);
+
+/* Attach the peer-state matrix.  state_dev: device, borrowed, must stay valid
+ * while the handle uses it.  row_stride_elems >= P.  Rows that start on 16-byte
+ * boundaries (state_dev and row_stride_elems*elem_size multiples of 16) take
+ * the 128-bit path; anything else is still correct through an element-wise
+ * path.  hip_stream: a hipStream_t, or NULL for the default stream. */
+int moshpit_bind_state(moshpit_ctx *h, void *state_dev, int64_t row_stride_elems, void *hip_stream);
+
+/* One averaging round t >= 0 (Alg. 1, one pass of its loop body; App. C.3's
+ * group-average formula with the group J_{i,t} of App. C.4).
+ * alive_host: host, N bytes, non-zero = the peer takes part; NULL = all do.
+ * The mask is copied before the call returns; the round itself is queued. */
+int moshpit_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host);
+
+/* Same, with the mask already in device memory (device, N bytes, must stay
+ * unchanged until the round has run; NULL = all peers take part). */
+int moshpit_round_dev(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev);
+
+/* Rounds t0 .. t0+rounds-1 (the loop of Alg. 1) under a failure schedule
+ * (NULL = nobody fails).  Masks are generated on the device.
+ * dist_out_host: NULL, or host array of rounds+1 doubles that receives the
+ *   average distortion (see moshpit_dist_to_mean) before the first round and
+ *   after every round.
+ * round_ms_out_host: NULL, or host array of `rounds` floats that receives the
+ *   GPU time of each round's averaging kernel in milliseconds.
+ * If either output array is given the call waits for the GPU before it
+ * returns; otherwise it only queues the work. */
+int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedule *s,
+                int32_t flags, double *dist_out_host, float *round_ms_out_host);
+
+/* Average distortion (1/N) * sum_i ||theta_i - theta_bar||^2 over all N rows,
+ * theta_bar = (1/N) sum_i theta_i (left-hand side of the equation of Thm 3.2;
+ * the error measure of Sec. 4.1).  Accumulated in binary64.  Waits for the
+ * GPU.  out_host: host, one double. */
+int moshpit_dist_to_mean(moshpit_ctx *h, double *out_host);
+
+/* Group key of every peer for round t (Eq. 1 on the static grid: the d-1
+ * coordinates other than t mod d, read in increasing coordinate order as a
+ * base-M number).  Computed on the device; waits.  keys_host: host, N int32. */
+int moshpit_group_keys(moshpit_ctx *h, int64_t t, int32_t *keys_host);
+
+/* The masks moshpit_run would use for rounds t0..t0+rounds-1 under schedule s,
+ * generated by the same device kernel; waits.
+ * masks_host: host, [rounds][N] bytes, 1 = alive. */
+int moshpit_schedule_mask(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t rounds,
+                          uint8_t *masks_host);
+
+/* Measurement aids (no counterpart in the paper).
+ *
+ * moshpit_set_tuning overrides the launch shape of the averaging kernel:
+ * cols = 128-bit vectors per thread per row, unroll = rows whose loads are
+ * issued before the first add; supported (cols, unroll) pairs are (1,4) (1,8)
+ * (1,16) (2,2) (2,4) (2,8) (4,2) (4,4); cols = unroll = 0 restores the default
+ * chosen from M and the dtype.  nontemporal: 1 = streaming loads/stores, 0 =
+ * plain, -1 = default.  Results never depend on nontemporal; they depend on
+ * unroll only through the (documented, fixed) summation tree.
+ *
+ * moshpit_copy_probe queues a plain 128-bit copy of nbytes (multiple of 16,
+ * both pointers device, 16-byte aligned) on hip_stream: the streaming ceiling
+ * the averaging kernel is compared with, and the known-size kernel used to
+ * calibrate HBM traffic counters. */
+int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t nontemporal);
+int moshpit_copy_probe(void *dst_dev, const void *src_dev, int64_t nbytes, void *hip_stream);
+
+/* Wait until everything queued on the bound stream has finished. */
+int moshpit_sync(moshpit_ctx *h);
+
+/* Message for the last error on this handle (library-owned, valid until the
+ * next call on the handle); "" if none.  h == NULL gives the message of the
+ * last failed moshpit_create on this thread. */
+const char *moshpit_last_error(moshpit_ctx *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOSHPIT_H */

@@ -1,0 +1,212 @@
+"""Thin ctypes binding of libmoshpit.so (see include/moshpit.h).
+
+Argument marshalling only: every step of a round runs in the library's HIP
+kernels.  PyTorch supplies device memory (the state tensor) and the stream.
+There is no fallback: if the library is missing or a call fails, an exception
+is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoshpit.so")
+
+F32, BF16 = 0, 1
+SCHED_NONE, SCHED_IID, SCHED_REJOIN, SCHED_EXPLICIT = 0, 1, 2, 3
+
+EXPORTS = [
+    "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",
+    "moshpit_run", "moshpit_dist_to_mean", "moshpit_group_keys", "moshpit_schedule_mask",
+    "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
+]
+
+
+class MoshpitError(RuntimeError):
+    pass
+
+
+class _CSchedule(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("down_rounds", ctypes.c_int32), ("p", ctypes.c_double),
+                ("seed", ctypes.c_uint64), ("explicit_masks", ctypes.c_void_p)]
+
+
+@dataclass
+class Schedule:
+    kind: int = SCHED_NONE
+    p: float = 0.0
+    seed: int = 0
+    down_rounds: int = 0
+    explicit_masks: np.ndarray | None = None      # uint8 [rounds, N] for SCHED_EXPLICIT
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libmoshpit.so (built in-tree by __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise MoshpitError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` to build it")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+    lib.moshpit_create.argtypes = [i64, i64, i32, i32, i32, ctypes.POINTER(vp)]
+    lib.moshpit_destroy.argtypes = [vp]
+    lib.moshpit_bind_state.argtypes = [vp, vp, i64, vp]
+    lib.moshpit_round.argtypes = [vp, i64, vp]
+    lib.moshpit_round_dev.argtypes = [vp, i64, vp]
+    lib.moshpit_run.argtypes = [vp, i64, i32, ctypes.POINTER(_CSchedule), i32, vp, vp]
+    lib.moshpit_dist_to_mean.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+    lib.moshpit_group_keys.argtypes = [vp, i64, vp]
+    lib.moshpit_schedule_mask.argtypes = [vp, ctypes.POINTER(_CSchedule), i64, i32, vp]
+    lib.moshpit_set_tuning.argtypes = [vp, i32, i32, i32]
+    lib.moshpit_copy_probe.argtypes = [vp, vp, i64, vp]
+    lib.moshpit_sync.argtypes = [vp]
+    lib.moshpit_last_error.argtypes = [vp]
+    lib.moshpit_last_error.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name != "moshpit_last_error":
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _c_schedule(s: Schedule | None, rounds: int, N: int):
+    if s is None:
+        return None, None
+    keep = None
+    ptr = None
+    if s.kind == SCHED_EXPLICIT:
+        keep = np.ascontiguousarray(s.explicit_masks, dtype=np.uint8)
+        if keep.shape != (rounds, N):
+            raise ValueError("explicit masks must have shape (rounds, N)")
+        ptr = keep.ctypes.data
+    return _CSchedule(s.kind, s.down_rounds, float(s.p), s.seed, ptr), keep
+
+
+class Moshpit:
+    """One handle = one peer-state matrix of N = M^d rows with P parameters."""
+
+    def __init__(self, N: int, P: int, M: int, d: int, dtype: int):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        rc = self._lib.moshpit_create(N, P, M, d, dtype, ctypes.byref(self._h))
+        if rc != 0:
+            msg = self._lib.moshpit_last_error(None).decode()
+            self._h = ctypes.c_void_p()
+            raise MoshpitError(f"moshpit_create failed ({rc}): {msg}")
+        self.N, self.P, self.M, self.d, self.dtype = N, P, M, d, dtype
+        self._state = None
+
+    # -- plumbing ---------------------------------------------------------
+    def _check(self, rc: int, what: str) -> None:
+        if rc != 0:
+            raise MoshpitError(f"{what} failed ({rc}): {self._lib.moshpit_last_error(self._h).decode()}")
+
+    def close(self) -> None:
+        if self._h:
+            self._lib.moshpit_destroy(self._h)
+            self._h = ctypes.c_void_p()
+            self._state = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the C ABI, one method per entry point ------------------------------
+    def bind_state(self, X, stream=None) -> None:
+        """X: torch tensor [N, P] on the GPU (float32 or bfloat16), unit column stride."""
+        import torch
+        want = torch.float32 if self.dtype == F32 else torch.bfloat16
+        if X.dtype != want or X.dim() != 2 or tuple(X.shape) != (self.N, self.P) or not X.is_cuda:
+            raise ValueError("state tensor has the wrong dtype, shape or device")
+        if X.stride(1) != 1:
+            raise ValueError("state tensor must have unit column stride")
+        if stream is None:
+            stream = torch.cuda.current_stream(X.device)
+        self._check(self._lib.moshpit_bind_state(self._h, X.data_ptr(), X.stride(0), stream.cuda_stream), "bind_state")
+        self._state = (X, stream)              # keep both alive
+
+    def bind_raw(self, ptr: int, row_stride: int, stream_handle: int = 0) -> None:
+        self._check(self._lib.moshpit_bind_state(self._h, ptr, row_stride, stream_handle), "bind_state")
+
+    def round(self, t: int, alive=None) -> None:
+        if alive is None:
+            self._check(self._lib.moshpit_round(self._h, t, None), "round")
+            return
+        a = np.ascontiguousarray(alive, dtype=np.uint8)
+        if a.shape != (self.N,):
+            raise ValueError("alive mask must have shape (N,)")
+        self._check(self._lib.moshpit_round(self._h, t, a.ctypes.data), "round")
+
+    def round_dev(self, t: int, alive_dev) -> None:
+        """alive_dev: torch uint8 tensor [N] on the GPU, or None."""
+        ptr = None
+        if alive_dev is not None:
+            if alive_dev.numel() != self.N or alive_dev.element_size() != 1 or not alive_dev.is_contiguous():
+                raise ValueError("device mask must be N contiguous bytes")
+            ptr = alive_dev.data_ptr()
+        self._check(self._lib.moshpit_round_dev(self._h, t, ptr), "round_dev")
+
+    def run(self, t0: int, rounds: int, schedule: Schedule | None = None, want_dist: bool = False,
+            want_times: bool = False, flags: int = 0):
+        cs, keep = _c_schedule(schedule, rounds, self.N)
+        dist = np.zeros(rounds + 1, dtype=np.float64) if want_dist else None
+        ms = np.zeros(rounds, dtype=np.float32) if want_times else None
+        rc = self._lib.moshpit_run(self._h, t0, rounds, ctypes.byref(cs) if cs is not None else None, flags,
+                                   dist.ctypes.data if want_dist else None, ms.ctypes.data if want_times else None)
+        self._check(rc, "run")
+        del keep
+        return dist, ms
+
+    def dist_to_mean(self) -> float:
+        out = ctypes.c_double()
+        self._check(self._lib.moshpit_dist_to_mean(self._h, ctypes.byref(out)), "dist_to_mean")
+        return out.value
+
+    def group_keys(self, t: int) -> np.ndarray:
+        keys = np.empty(self.N, dtype=np.int32)
+        self._check(self._lib.moshpit_group_keys(self._h, t, keys.ctypes.data), "group_keys")
+        return keys
+
+    def schedule_mask(self, schedule: Schedule | None, t0: int, rounds: int) -> np.ndarray:
+        cs, keep = _c_schedule(schedule, rounds, self.N)
+        masks = np.empty((rounds, self.N), dtype=np.uint8)
+        rc = self._lib.moshpit_schedule_mask(self._h, ctypes.byref(cs) if cs is not None else None, t0, rounds,
+                                             masks.ctypes.data)
+        self._check(rc, "schedule_mask")
+        del keep
+        return masks
+
+    def set_tuning(self, cols: int = 0, unroll: int = 0, nontemporal: int = -1) -> None:
+        self._check(self._lib.moshpit_set_tuning(self._h, cols, unroll, nontemporal), "set_tuning")
+
+    def sync(self) -> None:
+        self._check(self._lib.moshpit_sync(self._h), "sync")
+
+
+def copy_probe(dst, src, stream=None) -> None:
+    """Queue the library's plain copy kernel dst <- src (torch GPU tensors of equal byte size)."""
+    import torch
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("size mismatch")
+    if stream is None:
+        stream = torch.cuda.current_stream(src.device)
+    rc = load_library().moshpit_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream)
+    if rc != 0:
+        raise MoshpitError(f"copy_probe failed ({rc})")

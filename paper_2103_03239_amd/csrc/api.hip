@@ -1,0 +1,379 @@
+// C ABI of libmoshpit (include/moshpit.h): handle, argument checks, scratch,
+// and the order in which the kernels of a round / a run are queued.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/moshpit.h"
+#include "moshpit_internal.h"
+
+using namespace moshpit;
+
+struct moshpit_ctx {
+    int64_t N = 0, P = 0;
+    int32_t M = 0, d = 0, dtype = 0;
+    int device = 0;
+
+    void *X = nullptr;                 // borrowed
+    int64_t row_stride = 0;
+    hipStream_t stream = nullptr;
+
+    uint8_t *d_round_mask = nullptr;   // N bytes, for moshpit_round(host mask)
+    uint8_t *d_masks = nullptr;        // mask_rounds_cap * N bytes, for runs
+    int64_t mask_rounds_cap = 0;
+    int32_t *d_keys = nullptr;         // N
+    double *d_partials = nullptr;      // partials_cap doubles
+    int64_t partials_cap = 0;
+    double *d_dist = nullptr;          // dist_cap doubles
+    int64_t dist_cap = 0;
+    std::vector<hipEvent_t> events;    // 2 per timed round
+
+    MeanTuning tune;
+    char err[512] = {0};
+};
+
+namespace {
+
+thread_local char g_create_err[256] = {0};
+
+int fail(moshpit_ctx *h, int code, const char *fmt, ...)
+{
+    char *dst = h ? h->err : g_create_err;
+    const size_t cap = h ? sizeof(h->err) : sizeof(g_create_err);
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, cap, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(h, call)                                                                         \
+    do {                                                                                         \
+        hipError_t e_ = (call);                                                                  \
+        if (e_ != hipSuccess)                                                                    \
+            return fail((h), e_ == hipErrorOutOfMemory ? MOSHPIT_ENOMEM : MOSHPIT_EHIP,          \
+                        "%s: %s", #call, hipGetErrorString(e_));                                 \
+    } while (0)
+
+int64_t axis_stride(const moshpit_ctx *h, int64_t t)
+{
+    int64_t S = 1;
+    for (int64_t q = 0; q < t % h->d; ++q) S *= h->M;
+    return S;
+}
+
+int check_ready(moshpit_ctx *h)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    if (!h->X) return fail(h, MOSHPIT_ESTATE, "no state bound: call moshpit_bind_state first");
+    return MOSHPIT_OK;
+}
+
+int check_schedule(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t rounds)
+{
+    if (t0 < 0 || rounds < 0) return fail(h, MOSHPIT_EINVAL, "t0 and rounds must be >= 0");
+    if (!s) return MOSHPIT_OK;
+    if (s->kind < MOSHPIT_SCHED_NONE || s->kind > MOSHPIT_SCHED_EXPLICIT)
+        return fail(h, MOSHPIT_EINVAL, "unknown schedule kind %d", s->kind);
+    if (s->kind == MOSHPIT_SCHED_IID || s->kind == MOSHPIT_SCHED_REJOIN)
+        if (!(s->p >= 0.0 && s->p <= 1.0)) return fail(h, MOSHPIT_EINVAL, "failure probability outside [0,1]");
+    if (s->kind == MOSHPIT_SCHED_REJOIN && s->down_rounds < 1)
+        return fail(h, MOSHPIT_EINVAL, "down_rounds must be >= 1");
+    if (s->kind == MOSHPIT_SCHED_EXPLICIT && rounds > 0 && !s->explicit_masks)
+        return fail(h, MOSHPIT_EINVAL, "explicit schedule without masks");
+    return MOSHPIT_OK;
+}
+
+int reserve_masks(moshpit_ctx *h, int64_t rounds)
+{
+    if (rounds <= h->mask_rounds_cap) return MOSHPIT_OK;
+    if (h->d_masks) {
+        HIP_TRY(h, hipStreamSynchronize(h->stream));
+        HIP_TRY(h, hipFree(h->d_masks));
+        h->d_masks = nullptr;
+        h->mask_rounds_cap = 0;
+    }
+    HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_masks), static_cast<size_t>(rounds * h->N)));
+    h->mask_rounds_cap = rounds;
+    return MOSHPIT_OK;
+}
+
+int reserve_dist(moshpit_ctx *h, int64_t count)
+{
+    if (count <= h->dist_cap) return MOSHPIT_OK;
+    if (h->d_dist) {
+        HIP_TRY(h, hipStreamSynchronize(h->stream));
+        HIP_TRY(h, hipFree(h->d_dist));
+        h->d_dist = nullptr;
+        h->dist_cap = 0;
+    }
+    HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_dist), static_cast<size_t>(count) * sizeof(double)));
+    h->dist_cap = count;
+    return MOSHPIT_OK;
+}
+
+int reserve_events(moshpit_ctx *h, size_t count)
+{
+    while (h->events.size() < count) {
+        hipEvent_t ev;
+        HIP_TRY(h, hipEventCreate(&ev));
+        h->events.push_back(ev);
+    }
+    return MOSHPIT_OK;
+}
+
+// Fill d_masks[0..rounds) for rounds t0.. under schedule s (s may be NULL).
+int queue_masks(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t rounds)
+{
+    int rc = reserve_masks(h, rounds);
+    if (rc != MOSHPIT_OK || rounds == 0) return rc;
+    if (s && s->kind == MOSHPIT_SCHED_EXPLICIT) {
+        HIP_TRY(h, hipMemcpyAsync(h->d_masks, s->explicit_masks, static_cast<size_t>(rounds) * h->N,
+                                  hipMemcpyHostToDevice, h->stream));
+        return MOSHPIT_OK;
+    }
+    const int kind = s ? s->kind : MOSHPIT_SCHED_NONE;
+    const double p = s ? s->p : 0.0;
+    const uint32_t threshold = static_cast<uint32_t>(std::floor(p * 16777216.0));
+    HIP_TRY(h, launch_schedule(kind, threshold, s ? s->seed : 0, s ? s->down_rounds : 0, h->N, t0, rounds,
+                               h->d_masks, h->stream));
+    return MOSHPIT_OK;
+}
+
+int queue_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev)
+{
+    RoundGeom geom{h->N, h->M, axis_stride(h, t)};
+    HIP_TRY(h, launch_group_mean(h->X, h->dtype, h->P, h->row_stride, geom, alive_dev, h->tune, h->stream));
+    return MOSHPIT_OK;
+}
+
+int queue_dist(moshpit_ctx *h, double *out_dev)
+{
+    HIP_TRY(h, launch_dist_to_mean(h->X, h->dtype, h->N, h->P, h->row_stride, h->d_partials, out_dev, h->stream));
+    return MOSHPIT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int moshpit_create(int64_t N, int64_t P, int32_t M, int32_t d, int32_t dtype, moshpit_ctx **out)
+{
+    if (!out) return fail(nullptr, MOSHPIT_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (M < 2 || M > 64) return fail(nullptr, MOSHPIT_EINVAL, "M must be in [2, 64], got %d", M);
+    if (d < 1 || d > 62) return fail(nullptr, MOSHPIT_EINVAL, "d must be in [1, 62], got %d", d);
+    if (P < 1) return fail(nullptr, MOSHPIT_EINVAL, "P must be >= 1");
+    if (dtype != MOSHPIT_F32 && dtype != MOSHPIT_BF16) return fail(nullptr, MOSHPIT_EINVAL, "unknown dtype %d", dtype);
+    int64_t full = 1;
+    for (int q = 0; q < d; ++q) {
+        if (full > (int64_t(1) << 40) / M) return fail(nullptr, MOSHPIT_EINVAL, "M^d is too large");
+        full *= M;
+    }
+    if (N != full) return fail(nullptr, MOSHPIT_EINVAL, "N = %lld is not M^d = %lld", (long long)N, (long long)full);
+    if (N / M > 0x7fffffffLL) return fail(nullptr, MOSHPIT_EINVAL, "too many groups for 32-bit keys");
+
+    moshpit_ctx *h = new (std::nothrow) moshpit_ctx;
+    if (!h) return fail(nullptr, MOSHPIT_ENOMEM, "out of host memory");
+    h->N = N; h->P = P; h->M = M; h->d = d; h->dtype = dtype;
+    hipError_t e = hipGetDevice(&h->device);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&h->d_round_mask), static_cast<size_t>(N));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&h->d_keys), static_cast<size_t>(N) * sizeof(int32_t));
+    if (e != hipSuccess) {
+        fail(nullptr, e == hipErrorOutOfMemory ? MOSHPIT_ENOMEM : MOSHPIT_EHIP, "moshpit_create: %s",
+             hipGetErrorString(e));
+        const int code = e == hipErrorOutOfMemory ? MOSHPIT_ENOMEM : MOSHPIT_EHIP;
+        moshpit_destroy(h);
+        return code;
+    }
+    *out = h;
+    return MOSHPIT_OK;
+}
+
+int moshpit_destroy(moshpit_ctx *h)
+{
+    if (!h) return MOSHPIT_OK;
+    (void)hipStreamSynchronize(h->stream);
+    for (hipEvent_t ev : h->events) (void)hipEventDestroy(ev);
+    if (h->d_round_mask) (void)hipFree(h->d_round_mask);
+    if (h->d_masks) (void)hipFree(h->d_masks);
+    if (h->d_keys) (void)hipFree(h->d_keys);
+    if (h->d_partials) (void)hipFree(h->d_partials);
+    if (h->d_dist) (void)hipFree(h->d_dist);
+    delete h;
+    return MOSHPIT_OK;
+}
+
+int moshpit_bind_state(moshpit_ctx *h, void *state_dev, int64_t row_stride_elems, void *hip_stream)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    if (!state_dev) return fail(h, MOSHPIT_EINVAL, "state pointer is NULL");
+    if (row_stride_elems < h->P) return fail(h, MOSHPIT_EINVAL, "row stride %lld < P = %lld",
+                                             (long long)row_stride_elems, (long long)h->P);
+    const int64_t esize = h->dtype == MOSHPIT_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(state_dev) % esize != 0)
+        return fail(h, MOSHPIT_EINVAL, "state pointer is not aligned to the element size");
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, state_dev);
+    if (e != hipSuccess || attr.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return fail(h, MOSHPIT_EINVAL, "state pointer is not device memory");
+    }
+    if (h->X) HIP_TRY(h, hipStreamSynchronize(h->stream));
+    const int64_t need = dist_partials_count(h->dtype, h->P, row_stride_elems, state_dev);
+    if (need > h->partials_cap) {
+        if (h->d_partials) HIP_TRY(h, hipFree(h->d_partials));
+        h->d_partials = nullptr;
+        h->partials_cap = 0;
+        HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_partials), static_cast<size_t>(need) * sizeof(double)));
+        h->partials_cap = need;
+    }
+    int rc = reserve_dist(h, 64);
+    if (rc != MOSHPIT_OK) return rc;
+    h->X = state_dev;
+    h->row_stride = row_stride_elems;
+    h->stream = static_cast<hipStream_t>(hip_stream);
+    return MOSHPIT_OK;
+}
+
+int moshpit_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
+    if (!alive_host) return queue_round(h, t, nullptr);
+    HIP_TRY(h, hipMemcpyAsync(h->d_round_mask, alive_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice,
+                              h->stream));
+    // pageable host memory: the runtime has staged the bytes when the call returns
+    return queue_round(h, t, h->d_round_mask);
+}
+
+int moshpit_round_dev(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
+    return queue_round(h, t, alive_dev);
+}
+
+int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedule *s, int32_t flags,
+                double *dist_out_host, float *round_ms_out_host)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (flags != MOSHPIT_RUN_DEFAULT) return fail(h, MOSHPIT_EINVAL, "unknown flags 0x%x", flags);
+    rc = check_schedule(h, s, t0, rounds);
+    if (rc != MOSHPIT_OK) return rc;
+    const bool failures = s && s->kind != MOSHPIT_SCHED_NONE;
+    if (failures) {
+        rc = queue_masks(h, s, t0, rounds);
+        if (rc != MOSHPIT_OK) return rc;
+    }
+    if (dist_out_host) {
+        rc = reserve_dist(h, static_cast<int64_t>(rounds) + 1);
+        if (rc != MOSHPIT_OK) return rc;
+        rc = queue_dist(h, h->d_dist);
+        if (rc != MOSHPIT_OK) return rc;
+    }
+    if (round_ms_out_host) {
+        rc = reserve_events(h, 2 * static_cast<size_t>(rounds));
+        if (rc != MOSHPIT_OK) return rc;
+    }
+    for (int32_t r = 0; r < rounds; ++r) {
+        if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * r], h->stream));
+        rc = queue_round(h, t0 + r, failures ? h->d_masks + static_cast<int64_t>(r) * h->N : nullptr);
+        if (rc != MOSHPIT_OK) return rc;
+        if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * r + 1], h->stream));
+        if (dist_out_host) {
+            rc = queue_dist(h, h->d_dist + r + 1);
+            if (rc != MOSHPIT_OK) return rc;
+        }
+    }
+    if (dist_out_host || round_ms_out_host) {
+        if (dist_out_host)
+            HIP_TRY(h, hipMemcpyAsync(dist_out_host, h->d_dist, sizeof(double) * (static_cast<size_t>(rounds) + 1),
+                                      hipMemcpyDeviceToHost, h->stream));
+        HIP_TRY(h, hipStreamSynchronize(h->stream));
+        if (round_ms_out_host)
+            for (int32_t r = 0; r < rounds; ++r)
+                HIP_TRY(h, hipEventElapsedTime(&round_ms_out_host[r], h->events[2 * r], h->events[2 * r + 1]));
+    }
+    return MOSHPIT_OK;
+}
+
+int moshpit_dist_to_mean(moshpit_ctx *h, double *out_host)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (!out_host) return fail(h, MOSHPIT_EINVAL, "out is NULL");
+    rc = queue_dist(h, h->d_dist);
+    if (rc != MOSHPIT_OK) return rc;
+    HIP_TRY(h, hipMemcpyAsync(out_host, h->d_dist, sizeof(double), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return MOSHPIT_OK;
+}
+
+int moshpit_group_keys(moshpit_ctx *h, int64_t t, int32_t *keys_host)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    if (t < 0 || !keys_host) return fail(h, MOSHPIT_EINVAL, "bad round index or NULL output");
+    HIP_TRY(h, launch_group_keys(h->N, h->M, axis_stride(h, t), h->d_keys, h->stream));
+    HIP_TRY(h, hipMemcpyAsync(keys_host, h->d_keys, sizeof(int32_t) * static_cast<size_t>(h->N),
+                              hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return MOSHPIT_OK;
+}
+
+int moshpit_schedule_mask(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t rounds,
+                          uint8_t *masks_host)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    int rc = check_schedule(h, s, t0, rounds);
+    if (rc != MOSHPIT_OK) return rc;
+    if (rounds == 0) return MOSHPIT_OK;
+    if (!masks_host) return fail(h, MOSHPIT_EINVAL, "masks output is NULL");
+    rc = queue_masks(h, s, t0, rounds);
+    if (rc != MOSHPIT_OK) return rc;
+    HIP_TRY(h, hipMemcpyAsync(masks_host, h->d_masks, static_cast<size_t>(rounds) * h->N, hipMemcpyDeviceToHost,
+                              h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return MOSHPIT_OK;
+}
+
+int moshpit_sync(moshpit_ctx *h)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return MOSHPIT_OK;
+}
+
+int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t nontemporal)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    if (cols > 0 || unroll > 0) {
+        static const int ok[][2] = {{1, 4}, {1, 8}, {1, 16}, {2, 2}, {2, 4}, {2, 8}, {4, 2}, {4, 4}};
+        bool found = false;
+        for (const auto &pair : ok) found = found || (pair[0] == cols && pair[1] == unroll);
+        if (!found) return fail(h, MOSHPIT_EINVAL, "unsupported launch shape cols=%d unroll=%d", cols, unroll);
+    }
+    h->tune.cols = cols;
+    h->tune.unroll = unroll;
+    h->tune.nt = nontemporal;
+    return MOSHPIT_OK;
+}
+
+int moshpit_copy_probe(void *dst_dev, const void *src_dev, int64_t nbytes, void *hip_stream)
+{
+    if (!dst_dev || !src_dev || nbytes < 0 || nbytes % 16 != 0) return MOSHPIT_EINVAL;
+    if (reinterpret_cast<uintptr_t>(dst_dev) % 16 || reinterpret_cast<uintptr_t>(src_dev) % 16) return MOSHPIT_EINVAL;
+    return launch_copy_probe(dst_dev, src_dev, nbytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? MOSHPIT_OK
+               : MOSHPIT_EHIP;
+}
+
+const char *moshpit_last_error(moshpit_ctx *h) { return h ? h->err : g_create_err; }
+
+}  // extern "C"

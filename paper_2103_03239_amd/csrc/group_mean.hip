@@ -1,0 +1,302 @@
+// Group-mean round kernel for gfx950 (MI355X).
+//
+// One averaging round of Moshpit All-Reduce (Alg. 1, the AllReduce line; the
+// group-average formula of App. C.3 with the group J_{i,t} of App. C.4) on N
+// virtual peers stored as rows of X.  For round t the group g owns the M rows
+// base(g) + j*S, S = M^(t mod d); every row whose peer takes part is replaced
+// by the mean of the rows that take part.
+//
+// Mapping.  The reduction runs ACROSS rows, so each lane owns its columns for
+// the whole group and no cross-lane traffic or LDS is needed: a work item is
+// (group, column tile); a thread loads one 128-bit vector per participating
+// row (COLS of them, 256 lanes apart, to keep more loads in flight when M is
+// small), sums in binary32 registers, divides by the participant count and
+// stores the mean to the same rows.  Rows of absent peers are never touched,
+// so HBM traffic is 2 * elem_size * P bytes per participating peer.  In-place
+// is safe because a work item reads and writes only its own (group, tile) and
+// all its loads retire before its first store.
+//
+// The participant bitmap of a group is built by the wave itself: lane j < M
+// reads alive[base + j*S] and a ballot gives a 64-bit mask (hence M <= 64).
+#include "moshpit_internal.h"
+
+namespace moshpit {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = 256;
+
+__device__ __forceinline__ uint32_t bf16_bits_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // keep NaN a NaN
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// How VE elements of storage type DT travel as one memory access and widen to
+// binary32.
+template <int DT, int VE> struct Vec;
+
+template <> struct Vec<0, 4> {
+    typedef f32x4 mem_t;
+    static constexpr int NE = 4;
+    static __device__ __forceinline__ mem_t zero() { return mem_t{0.f, 0.f, 0.f, 0.f}; }
+    static __device__ __forceinline__ void widen(const mem_t &m, float (&f)[NE])
+    {
+        f[0] = m.x; f[1] = m.y; f[2] = m.z; f[3] = m.w;
+    }
+    static __device__ __forceinline__ mem_t narrow(const float (&f)[NE]) { return mem_t{f[0], f[1], f[2], f[3]}; }
+};
+
+template <> struct Vec<0, 1> {
+    typedef float mem_t;
+    static constexpr int NE = 1;
+    static __device__ __forceinline__ mem_t zero() { return 0.f; }
+    static __device__ __forceinline__ void widen(const mem_t &m, float (&f)[NE]) { f[0] = m; }
+    static __device__ __forceinline__ mem_t narrow(const float (&f)[NE]) { return f[0]; }
+};
+
+template <> struct Vec<1, 8> {
+    typedef u32x4 mem_t;
+    static constexpr int NE = 8;
+    static __device__ __forceinline__ mem_t zero() { return mem_t{0u, 0u, 0u, 0u}; }
+    static __device__ __forceinline__ void widen(const mem_t &m, float (&f)[NE])
+    {
+        const uint32_t w[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f[2 * k] = __uint_as_float(w[k] << 16);             // even element: low half
+            f[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u); // odd element: high half
+        }
+    }
+    static __device__ __forceinline__ mem_t narrow(const float (&f)[NE])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w[k] = bf16_bits_rne(f[2 * k]) | (bf16_bits_rne(f[2 * k + 1]) << 16);
+        return mem_t{w[0], w[1], w[2], w[3]};
+    }
+};
+
+template <> struct Vec<1, 1> {
+    typedef uint16_t mem_t;
+    static constexpr int NE = 1;
+    static __device__ __forceinline__ mem_t zero() { return 0; }
+    static __device__ __forceinline__ void widen(const mem_t &m, float (&f)[NE])
+    {
+        f[0] = __uint_as_float(static_cast<uint32_t>(m) << 16);
+    }
+    static __device__ __forceinline__ mem_t narrow(const float (&f)[NE])
+    {
+        return static_cast<uint16_t>(bf16_bits_rne(f[0]));
+    }
+};
+
+template <bool NT, typename T> __device__ __forceinline__ T load_vec(const T *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT, typename T> __device__ __forceinline__ void store_vec(T *p, const T &v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// X            state, byte pointer to element (row 0, first column of this launch)
+// row_bytes    distance between rows in bytes
+// nvec         vectors of VE elements per row covered by this launch
+// tiles        ceil(nvec / (kBlock * COLS))
+// work_items   (N / M) * tiles
+template <int DT, int VE, int COLS, int U, bool NT>
+__global__ __launch_bounds__(kBlock) void group_mean_kernel(char *X, int64_t row_bytes, int64_t nvec,
+                                                            const uint8_t *__restrict__ alive, int32_t M,
+                                                            int64_t S, int64_t tiles, int64_t work_items)
+{
+    typedef Vec<DT, VE> V;
+    typedef typename V::mem_t mem_t;
+    constexpr int NE = V::NE;
+    const int lane = threadIdx.x & 63;
+
+    for (int64_t w = blockIdx.x; w < work_items; w += gridDim.x) {
+        const int64_t g = w / tiles;
+        const int64_t tile = w - g * tiles;
+        const int64_t base = (g / S) * S * M + (g % S);
+
+        bool takes_part = false;
+        if (lane < M) takes_part = (alive == nullptr) || (alive[base + static_cast<int64_t>(lane) * S] != 0);
+        const uint64_t live = __ballot(takes_part);
+        const int cnt = __popcll(live);
+        if (cnt < 2) continue;                       // nothing to average: rows stay as they are
+
+        const int64_t v0 = tile * (kBlock * COLS) + threadIdx.x;
+        bool in_row[COLS];
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) in_row[c] = (v0 + c * kBlock) < nvec;
+
+        char *gbase = X + base * row_bytes + v0 * static_cast<int64_t>(sizeof(mem_t));
+        const int64_t jstep = S * row_bytes;
+
+        float acc[COLS][NE];
+#pragma unroll
+        for (int c = 0; c < COLS; ++c)
+#pragma unroll
+            for (int e = 0; e < NE; ++e) acc[c][e] = 0.f;
+
+        uint64_t rem = live;
+        while (rem != 0) {
+            mem_t buf[U][COLS];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int c = 0; c < COLS; ++c) buf[u][c] = V::zero();
+                if (rem != 0) {
+                    const int j = __builtin_ctzll(rem);
+                    rem &= rem - 1;
+                    const mem_t *src = reinterpret_cast<const mem_t *>(gbase + j * jstep);
+#pragma unroll
+                    for (int c = 0; c < COLS; ++c)
+                        if (in_row[c]) buf[u][c] = load_vec<NT>(src + c * kBlock);
+                }
+            }
+            // fixed-shape pairwise tree over the U slots (absent slots hold 0)
+#pragma unroll
+            for (int c = 0; c < COLS; ++c) {
+                float f[U][NE];
+#pragma unroll
+                for (int u = 0; u < U; ++u) V::widen(buf[u][c], f[u]);
+#pragma unroll
+                for (int s = 1; s < U; s *= 2)
+#pragma unroll
+                    for (int u = 0; u + s < U; u += 2 * s)
+#pragma unroll
+                        for (int e = 0; e < NE; ++e) f[u][e] += f[u + s][e];
+#pragma unroll
+                for (int e = 0; e < NE; ++e) acc[c][e] += f[0][e];
+            }
+        }
+
+        const float k = static_cast<float>(cnt);
+        mem_t mean[COLS];
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) acc[c][e] = acc[c][e] / k;
+            mean[c] = V::narrow(acc[c]);
+        }
+
+        rem = live;
+        while (rem != 0) {
+            const int j = __builtin_ctzll(rem);
+            rem &= rem - 1;
+            mem_t *dst = reinterpret_cast<mem_t *>(gbase + j * jstep);
+#pragma unroll
+            for (int c = 0; c < COLS; ++c)
+                if (in_row[c]) store_vec<NT>(dst + c * kBlock, mean[c]);
+        }
+    }
+}
+
+template <int DT, int VE, int COLS, int U, bool NT>
+hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *alive, const RoundGeom &geom,
+                      hipStream_t stream)
+{
+    if (nvec <= 0) return hipSuccess;
+    const int64_t tiles = (nvec + kBlock * COLS - 1) / (kBlock * COLS);
+    const int64_t work = (geom.N / geom.M) * tiles;
+    const int64_t grid = work < 0x7fffffffLL ? work : 0x7fffffffLL;
+    group_mean_kernel<DT, VE, COLS, U, NT><<<dim3(static_cast<uint32_t>(grid)), dim3(kBlock), 0, stream>>>(
+        X, row_bytes, nvec, alive, geom.M, geom.S, tiles, work);
+    return hipGetLastError();
+}
+
+template <int DT, int VE>
+hipError_t launch_shape(int cols, int unroll, bool nt, char *X, int64_t row_bytes, int64_t nvec,
+                        const uint8_t *alive, const RoundGeom &geom, hipStream_t stream)
+{
+#define MOSHPIT_CASE(C, UU)                                                                          \
+    if (cols == C && unroll == UU)                                                                   \
+        return nt ? launch_one<DT, VE, C, UU, true>(X, row_bytes, nvec, alive, geom, stream)         \
+                  : launch_one<DT, VE, C, UU, false>(X, row_bytes, nvec, alive, geom, stream);
+    MOSHPIT_CASE(1, 4)
+    MOSHPIT_CASE(1, 8)
+    MOSHPIT_CASE(1, 16)
+    MOSHPIT_CASE(2, 2)
+    MOSHPIT_CASE(2, 4)
+    MOSHPIT_CASE(2, 8)
+    MOSHPIT_CASE(4, 2)
+    MOSHPIT_CASE(4, 4)
+#undef MOSHPIT_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, const RoundGeom &geom,
+                             const uint8_t *alive, const MeanTuning &tune, hipStream_t stream)
+{
+    const int64_t esize = dtype == 0 ? 4 : 2;
+    const int64_t row_bytes = row_stride * esize;
+    const bool aligned = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (row_bytes % 16 == 0);
+    const int64_t ve = dtype == 0 ? 4 : 8;
+    const int64_t nvec = aligned ? P / ve : 0;          // 128-bit part of every row
+    const int64_t tail0 = nvec * ve;                    // first column of the element-wise part
+
+    int cols = tune.cols, unroll = tune.unroll;
+    if (cols <= 0 || unroll <= 0) {
+        // aim for ~16 independent 128-bit loads per lane before the first add
+        if (geom.M >= 8) { unroll = 8; cols = dtype == 0 ? 2 : 1; }
+        else if (geom.M >= 4) { unroll = 4; cols = dtype == 0 ? 4 : 2; }
+        else { unroll = 2; cols = 4; }
+    }
+    const bool nt = tune.nt > 0;
+
+    char *base = static_cast<char *>(X);
+    hipError_t e = hipSuccess;
+    if (nvec > 0) {
+        e = dtype == 0 ? launch_shape<0, 4>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, stream)
+                       : launch_shape<1, 8>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, stream);
+        if (e != hipSuccess) return e;
+    }
+    if (tail0 < P) {
+        char *tbase = base + tail0 * esize;
+        e = dtype == 0 ? launch_one<0, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, stream)
+                       : launch_one<1, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, stream);
+    }
+    return e;
+}
+
+// ---- plain copy, the streaming ceiling the round kernel is measured against ----
+
+namespace {
+__global__ __launch_bounds__(kBlock) void copy_probe_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
+                                                            int64_t nvec)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock * 4;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock * 4 + threadIdx.x; i < nvec; i += stride) {
+        u32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * kBlock < nvec) v[u] = src[i + u * kBlock];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * kBlock < nvec) dst[i + u * kBlock] = v[u];
+    }
+}
+}  // namespace
+
+hipError_t launch_copy_probe(void *dst, const void *src, int64_t nbytes, hipStream_t stream)
+{
+    const int64_t nvec = nbytes / 16;
+    if (nvec <= 0) return hipSuccess;
+    int64_t blocks = (nvec + kBlock * 4 - 1) / (kBlock * 4);
+    if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
+    copy_probe_kernel<<<dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0, stream>>>(
+        static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), nvec);
+    return hipGetLastError();
+}
+
+}  // namespace moshpit

@@ -1,0 +1,52 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernel
+// translation units.  Not installed; the public interface is include/moshpit.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moshpit {
+
+// Launch shape of the group-mean kernel.  cols = 128-bit vectors per thread per
+// row, unroll = rows whose loads are issued before the first add, nt =
+// non-temporal loads and stores.  0 / -1 mean "choose from M and the dtype".
+struct MeanTuning {
+    int cols = 0;
+    int unroll = 0;
+    int nt = -1;
+    int block = 0;
+};
+
+// Geometry of one round: group g (0 <= g < N/M) owns rows base(g) + j*S,
+// j = 0..M-1, with S = M^(t mod d) and base(g) = (g / S) * S * M + g % S.
+struct RoundGeom {
+    int64_t N;
+    int32_t M;
+    int64_t S;
+};
+
+// Queue one averaging round on `stream`.  X: device, row-major, `P` valid
+// elements per row, rows `row_stride` elements apart.  alive: device, N bytes
+// (non-zero = takes part) or nullptr (all take part).
+hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, const RoundGeom &geom,
+                             const uint8_t *alive, const MeanTuning &tune, hipStream_t stream);
+
+// Number of partial sums launch_dist_partials writes for this shape.
+int64_t dist_partials_count(int dtype, int64_t P, int64_t row_stride, const void *X);
+
+// Queue the distortion reduction: partials (device, dist_partials_count
+// doubles) then out[0] = (sum of partials) / N.
+hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, int64_t row_stride,
+                               double *partials, double *out, hipStream_t stream);
+
+// Queue the failure-schedule generator: masks[r][i] (device, rounds*N bytes).
+hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down, int64_t N, int64_t t0,
+                           int rounds, uint8_t *masks, hipStream_t stream);
+
+// Queue the group-key kernel: keys[i] (device, N int32) for axis a, S = M^a.
+hipError_t launch_group_keys(int64_t N, int32_t M, int64_t S, int32_t *keys, hipStream_t stream);
+
+// Queue a plain 128-bit copy of nbytes (multiple of 16) from src to dst.
+hipError_t launch_copy_probe(void *dst, const void *src, int64_t nbytes, hipStream_t stream);
+
+}  // namespace moshpit

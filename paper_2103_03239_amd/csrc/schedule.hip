@@ -1,0 +1,79 @@
+// Integer side of a round on the device: the seeded failure schedule and the
+// group keys (Eq. 1 on the static grid).  Pure 64-bit integer arithmetic, so
+// results are bit-exact and independent of launch shape.
+#include "moshpit_internal.h"
+
+namespace moshpit {
+namespace {
+
+// Counter-based generator of the failure events (the paper only says that a
+// peer fails in a round with probability p, Sec. 4.1; the mixer is this
+// library's own and is stated in the public header).
+__device__ __forceinline__ uint64_t mix64(uint64_t x)
+{
+    x ^= x >> 32; x *= 0x9E3779B97F4A7C15ull;
+    x ^= x >> 29; x *= 0x6A09E667F3BCC909ull;
+    x ^= x >> 32;
+    return x;
+}
+
+__device__ __forceinline__ bool failure_event(uint64_t seed, int64_t s, int64_t i, uint32_t threshold)
+{
+    const uint64_t round_key = mix64(seed + 0x9E3779B97F4A7C15ull * static_cast<uint64_t>(s + 1));
+    const uint64_t u = mix64(round_key ^ static_cast<uint64_t>(i));
+    return static_cast<uint32_t>(u >> 40) < threshold;
+}
+
+// One thread per peer; the thread walks the rounds because a peer's absence
+// depends on when its last one started (kind 2).
+__global__ __launch_bounds__(256) void schedule_kernel(int kind, uint32_t threshold, uint64_t seed, int down,
+                                                       int64_t N, int64_t t0, int rounds,
+                                                       uint8_t *__restrict__ masks)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= N) return;
+    if (kind == 0) {
+        for (int r = 0; r < rounds; ++r) masks[static_cast<int64_t>(r) * N + i] = 1;
+    } else if (kind == 1) {
+        for (int r = 0; r < rounds; ++r)
+            masks[static_cast<int64_t>(r) * N + i] = failure_event(seed, t0 + r, i, threshold) ? 0 : 1;
+    } else {
+        int away = 0;                                    // rounds still to sit out
+        for (int64_t s = 0; s < t0 + rounds; ++s) {
+            if (away == 0 && failure_event(seed, s, i, threshold)) away = down;
+            const uint8_t present = away == 0 ? 1 : 0;
+            if (away > 0) --away;
+            if (s >= t0) masks[(s - t0) * N + i] = present;
+        }
+    }
+}
+
+// key(i) = the base-M number formed by the digits of i other than digit a,
+// i.e. floor(i / (S*M)) * S + i mod S with S = M^a.
+__global__ __launch_bounds__(256) void group_keys_kernel(int64_t N, int32_t M, int64_t S, int32_t *__restrict__ keys)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= N) return;
+    keys[i] = static_cast<int32_t>((i / (S * M)) * S + (i % S));
+}
+
+}  // namespace
+
+hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down, int64_t N, int64_t t0,
+                           int rounds, uint8_t *masks, hipStream_t stream)
+{
+    if (N <= 0 || rounds <= 0) return hipSuccess;
+    const uint32_t blocks = static_cast<uint32_t>((N + 255) / 256);
+    schedule_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(kind, threshold, seed, down, N, t0, rounds, masks);
+    return hipGetLastError();
+}
+
+hipError_t launch_group_keys(int64_t N, int32_t M, int64_t S, int32_t *keys, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    const uint32_t blocks = static_cast<uint32_t>((N + 255) / 256);
+    group_keys_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(N, M, S, keys);
+    return hipGetLastError();
+}
+
+}  // namespace moshpit

@@ -1,0 +1,250 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle,
+element by element on the same seeded inputs.
+
+Small cases compare the whole state; the five full-size workloads compare a
+sample of whole columns (columns never interact, so the oracle can compute any
+column on its own) plus properties that hold at any size.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moshpit_oracle as orc
+from paper_2103_03239_amd import binding, inputs
+from parity_util import TOL, assert_dist_close, assert_state_close, dist_floor, sample_columns
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def sched_of(w):
+    return binding.Schedule(kind=w.kind, p=w.p, seed=w.mask_seed, down_rounds=w.down)
+
+
+def to_f64(X):
+    return X.detach().to("cpu").to(torch.float64).numpy()
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# --------------------------------------------------------------------------
+# integer work: keys and masks, bit-exact
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,d", [(4, 2), (16, 2), (4, 3), (32, 2), (16, 3), (2, 5), (3, 4), (64, 1), (7, 2)])
+def test_group_keys_bit_exact(M, d):
+    N = M ** d
+    with binding.Moshpit(N, 8, M, d, binding.F32) as m:
+        for t in range(2 * d + 1):
+            say(f"keys M={M} d={d} t={t}")
+            assert np.array_equal(m.group_keys(t), orc.group_keys(N, M, d, t))
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_schedule_masks_bit_exact(cfg):
+    w = inputs.CONFIGS[cfg]
+    with binding.Moshpit(w.N, 8, w.M, w.d, w.dtype) as m:
+        for t0, rounds in ((0, w.rounds), (5, 9), (0, 0)):
+            say(f"masks {w.name} t0={t0} rounds={rounds}")
+            got = m.schedule_mask(sched_of(w), t0, rounds)
+            want = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, w.N, t0, rounds)
+            assert np.array_equal(got, want)
+        # p = 0 and p = 1 corner thresholds
+        for p in (0.0, 1.0, 0.5):
+            s = binding.Schedule(kind=binding.SCHED_IID, p=p, seed=9)
+            assert np.array_equal(m.schedule_mask(s, 2, 3), orc.schedule_masks(1, p, 9, 0, w.N, 2, 3))
+
+
+# --------------------------------------------------------------------------
+# whole-state parity on small shapes
+# --------------------------------------------------------------------------
+
+SMALL = [
+    # M, d, P, dtype, row_stride, offset_elems, p
+    (4, 2, 65_536, 0, None, 0, 0.0),        # workload 1 itself
+    (16, 2, 5_000, 0, None, 0, 0.05),       # several tiles + ragged last tile
+    (4, 3, 9_999, 0, 10_000, 0, 0.1),       # P not a multiple of 4: element-wise tail
+    (32, 2, 3_001, 0, 3_004, 0, 0.2),       # M = 32, padded stride
+    (16, 3, 2_056, 1, None, 0, 0.1),        # bf16, 4096 peers
+    (16, 2, 1_003, 1, 1_008, 0, 0.3),       # bf16 ragged tail, padded stride
+    (3, 3, 777, 0, None, 0, 0.25),          # M not a power of two, unaligned rows (777*4 % 16 != 0)
+    (2, 6, 1_030, 1, None, 0, 0.3),         # M = 2, bf16 unaligned rows (1030*2 % 16 != 0)
+    (64, 1, 2_048, 0, None, 0, 0.1),        # one group of 64 (bit 63 of the live bitmap)
+    (5, 2, 1, 0, None, 0, 0.2),             # a single column
+    (8, 2, 4_096, 0, 4_100, 1, 0.1),        # base pointer not 16-byte aligned
+    (7, 2, 20_000, 1, 20_000, 3, 0.15),     # bf16, base pointer 6 bytes off, M = 7
+]
+
+
+@pytest.mark.parametrize("M,d,P,dtype,stride,offset,p", SMALL)
+def test_small_full_state(M, d, P, dtype, stride, offset, p):
+    N = M ** d
+    rounds = 2 * d + 1
+    w = inputs.Workload(f"small-{M}-{d}-{P}", N, M, d, P, dtype, "peer_offset",
+                        inputs.KIND_IID if p > 0 else inputs.KIND_NONE, p, 0, rounds, 42 + M + P, 4242 + P)
+    say(f"case {w}")
+    stride = P if stride is None else stride
+    buf = torch.full((N * stride + offset + 64,), 777.0, dtype=w.torch_dtype, device=DEV)
+    X = buf[offset: offset + N * stride].view(N, stride)[:, :P]
+    X.copy_(inputs.make_state(w, DEV))
+    ref = to_f64(X).copy()
+    masks = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, N, 0, rounds)
+    dist_ref = orc.run(ref, M, d, 0, rounds, masks, want_dist=True)
+
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(X)
+        dist, ms = m.run(0, rounds, sched_of(w), want_dist=True, want_times=True)
+    assert_state_close(to_f64(X), ref, TOL[dtype], w.name)
+    assert_dist_close(dist, dist_ref, TOL[dtype], dist_floor(P, dtype, 1.0), w.name)
+    assert (ms >= 0).all()
+    # padding and guard elements were never written
+    whole = buf.to(torch.float32).cpu().numpy()
+    assert (whole[:offset] == 777.0).all() and (whole[offset + N * stride:] == 777.0).all()
+    if stride > P:
+        pad = whole[offset: offset + N * stride].reshape(N, stride)[:, P:]
+        assert (pad == 777.0).all()
+
+
+def test_workload1_is_exact_global_mean():
+    """Full grid, no failures, d rounds: every peer ends on the global mean
+    (exact-average theorem, App. C.1); distortion follows M^-k - M^-d."""
+    w = inputs.CONFIGS[1]
+    X = inputs.make_state(w, DEV)
+    X0 = to_f64(X)
+    with binding.Moshpit(w.N, w.P, w.M, w.d, w.dtype) as m:
+        m.bind_state(X)
+        dist, _ = m.run(0, w.rounds, None, want_dist=True)
+    want = X0.mean(axis=0)
+    assert_state_close(to_f64(X), np.broadcast_to(want, X0.shape), TOL[0], w.name)
+    assert abs(dist[0] / w.P - (1 - 1 / 16)) < 0.02
+    assert abs(dist[1] / w.P - (1 / 4 - 1 / 16)) < 0.02 * (1 / 4 - 1 / 16)
+    assert dist[2] <= dist_floor(w.P, 0, 1.0)
+
+
+def test_round_entry_points_and_special_masks():
+    """moshpit_round (host mask), moshpit_round_dev (device mask), explicit
+    schedules; all-dead and one-survivor-per-group rounds change nothing."""
+    M, d, P = 4, 2, 3000
+    N = 16
+    w = inputs.Workload("rounds", N, M, d, P, 0, "normal", 0, 0.0, 0, 0, 7, 7)
+    X = inputs.make_state(w, DEV)
+    X0 = X.clone()
+    ref = to_f64(X).copy()
+    rng = np.random.default_rng(0)
+    with binding.Moshpit(N, P, M, d, 0) as m:
+        m.bind_state(X)
+        m.round(0, np.zeros(N, np.uint8))
+        one = np.zeros(N, np.uint8)
+        one[[1, 6, 8, 15]] = 1
+        m.round(0, one)
+        m.sync()
+        assert torch.equal(X, X0)
+        masks = (rng.random((5, N)) > 0.3).astype(np.uint8)
+        for t in range(5):
+            if t % 2 == 0:
+                m.round(t, masks[t])
+            else:
+                m.round_dev(t, torch.from_numpy(masks[t]).to(DEV))
+            orc.round_(ref, M, d, t, masks[t])
+        m.round(5)                      # NULL mask: everybody
+        orc.round_(ref, M, d, 5)
+        m.sync()
+        assert_state_close(to_f64(X), ref, 1e-6, "round entry points")
+        # the same five rounds as one explicit schedule reproduce the same bits
+        Y = X0.clone()
+        m.bind_state(Y)
+        m.run(0, 5, binding.Schedule(kind=binding.SCHED_EXPLICIT, explicit_masks=masks))
+        m.round_dev(5, None)
+        m.sync()
+        assert torch.equal(Y, X)
+        assert abs(m.dist_to_mean() - orc.dist_to_mean(ref)) <= 1e-6 * orc.dist_to_mean(ref) + dist_floor(P, 0, 1.0)
+
+
+def test_errors_are_reported_not_crashed():
+    with binding.Moshpit(16, 100, 4, 2, 0) as m:
+        with pytest.raises(binding.MoshpitError):
+            m.round(0)                                    # nothing bound
+        X = torch.zeros(16, 100, device=DEV)
+        m.bind_state(X)
+        with pytest.raises(binding.MoshpitError):
+            m.round(-1)
+        with pytest.raises(binding.MoshpitError):
+            m.run(0, 2, binding.Schedule(kind=binding.SCHED_IID, p=1.5))
+        with pytest.raises(binding.MoshpitError):
+            m.run(0, 2, binding.Schedule(kind=binding.SCHED_REJOIN, p=0.1, down_rounds=0))
+        with pytest.raises(binding.MoshpitError):
+            m.bind_raw(X.data_ptr(), 50)                  # stride < P
+        with pytest.raises(binding.MoshpitError):
+            m.set_tuning(3, 3)
+        m.run(0, 0)                                       # zero rounds is a no-op
+        m.sync()
+
+
+@pytest.mark.parametrize("cols,unroll,nt", [(1, 4, 0), (1, 8, 1), (1, 16, 0), (2, 2, 1), (2, 4, 0), (2, 8, 1),
+                                            (4, 2, 0), (4, 4, 1)])
+def test_every_launch_shape(cols, unroll, nt):
+    """All launch shapes of the averaging kernel meet the same parity bar."""
+    for dtype, M, d, P in ((0, 16, 2, 6_001), (1, 4, 3, 9_000)):
+        N = M ** d
+        w = inputs.Workload("shape", N, M, d, P, dtype, "normal", 1, 0.2, 0, 5, 5, 6)
+        say(f"shape cols={cols} unroll={unroll} nt={nt} dtype={dtype}")
+        X = inputs.make_state(w, DEV, row_stride=P + (8 - P % 8) % 8)
+        ref = to_f64(X).copy()
+        masks = orc.schedule_masks(1, 0.2, 6, 0, N, 0, 5)
+        orc.run(ref, M, d, 0, 5, masks)
+        with binding.Moshpit(N, P, M, d, dtype) as m:
+            m.bind_state(X)
+            m.set_tuning(cols, unroll, nt)
+            m.run(0, 5, sched_of(w))
+            m.sync()
+        assert_state_close(to_f64(X), ref, TOL[dtype], "launch shape")
+
+
+# --------------------------------------------------------------------------
+# the five workloads at full size
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_full_size_workload(cfg):
+    w = inputs.CONFIGS[cfg]
+    say(f"full-size {w.name}: generating {w.N}x{w.P}")
+    X = inputs.make_state(w, DEV)
+    cols = sample_columns(w.P, 1024 if w.N >= 1024 else 4096, seed=cfg)
+    cols_dev = torch.from_numpy(cols).to(DEV)
+    ref = to_f64(X.index_select(1, cols_dev)).copy()
+    colsum0 = X.sum(dim=0, dtype=torch.float64)
+    rms0 = float(np.sqrt((ref ** 2).mean()))
+
+    masks_ref = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, w.N, 0, w.rounds)
+    orc.run(ref, w.M, w.d, 0, w.rounds, masks_ref, threads=8, slab=128)
+
+    with binding.Moshpit(w.N, w.P, w.M, w.d, w.dtype) as m:
+        m.bind_state(X)
+        assert np.array_equal(m.schedule_mask(sched_of(w), 0, w.rounds), masks_ref)
+        say("  running")
+        dist, ms = m.run(0, w.rounds, sched_of(w), want_dist=True, want_times=True)
+        say(f"  round ms: {np.round(ms, 3).tolist()}")
+        say(f"  dist/P  : {(dist / w.P).tolist()}")
+    worst = assert_state_close(to_f64(X.index_select(1, cols_dev)), ref, TOL[w.dtype], w.name)
+    say(f"  worst sampled row error {worst:.3e}")
+
+    # properties that hold at any size
+    # (a) the distortion never grows (Jensen; proof sketch of Thm 3.1)
+    slack = TOL[w.dtype] * dist[0] + dist_floor(w.P, w.dtype, rms0)
+    assert (np.diff(dist) <= slack).all(), dist
+    # (b) every column sum is preserved by every round, whatever the masks
+    colsum = X.sum(dim=0, dtype=torch.float64)
+    scale = rms0 * np.sqrt(w.N)
+    drift = float((colsum - colsum0).abs().max()) / scale
+    say(f"  column-sum drift / (rms*sqrt(N)) = {drift:.3e}")
+    assert drift <= (1e-5 if w.dtype == 0 else 0.05)
+    # (c) the distortion of the sampled columns alone agrees with the oracle's
+    got_sub = X.index_select(1, cols_dev).to(torch.float64)
+    sub = float(((got_sub - got_sub.mean(dim=0)) ** 2).sum() / w.N)
+    want_sub = orc.dist_to_mean(ref)
+    assert abs(sub - want_sub) <= 10 * TOL[w.dtype] * want_sub + dist_floor(len(cols), w.dtype, rms0)
+    if w.kind == 0:
+        assert dist[-1] <= dist_floor(w.P, w.dtype, rms0)
