@@ -8,11 +8,17 @@ import numpy as np
 TOL = {0: 1e-6, 1: 1e-2}
 # Storage epsilon (unit roundoff) of the two state types.
 EPS = {0: 2.0 ** -24, 1: 2.0 ** -9}
+ELEM_FACTOR = 8.0
 
 
 def assert_state_close(got: np.ndarray, want: np.ndarray, tol: float, what: str = "") -> float:
-    """Per-row relative L2 error <= tol, and every element within
-    tol * (|want| + rms of its row).  Returns the worst row error."""
+    """The parity bar: per-row relative L2 error <= tol.  On top of it an
+    outlier guard: every element within ELEM_FACTOR * tol * (|want| + rms of
+    its row).  The row error is a one-sigma measure of the (storage-rounding)
+    noise while the largest of 1e5..1e9 element errors sits 4-6 sigma out, so
+    the guard is wider than the bar; a wrong element (an error of order rms) is
+    still >= 1e2 (bf16) / 1e5 (fp32) times outside it.  Returns the worst row
+    error."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape
@@ -24,9 +30,9 @@ def assert_state_close(got: np.ndarray, want: np.ndarray, tol: float, what: str 
     worst = float(rel.max())
     assert worst <= tol, f"{what}: worst row relative error {worst:.3e} > {tol:.1e} (row {int(rel.argmax())})"
     rms = norm / np.sqrt(want.shape[1])
-    bound = tol * (np.abs(want) + rms[:, None])
+    bound = ELEM_FACTOR * tol * (np.abs(want) + rms[:, None])
     bad = np.abs(got - want) > bound
-    assert not bad.any(), (f"{what}: {int(bad.sum())} elements outside tol*(|x|+rms); first at "
+    assert not bad.any(), (f"{what}: {int(bad.sum())} elements outside {ELEM_FACTOR}*tol*(|x|+rms); first at "
                            f"{tuple(np.argwhere(bad)[0])}")
     return worst
 

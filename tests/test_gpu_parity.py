@@ -87,7 +87,7 @@ def test_small_full_state(M, d, P, dtype, stride, offset, p):
                         inputs.KIND_IID if p > 0 else inputs.KIND_NONE, p, 0, rounds, 42 + M + P, 4242 + P)
     say(f"case {w}")
     stride = P if stride is None else stride
-    buf = torch.full((N * stride + offset + 64,), 777.0, dtype=w.torch_dtype, device=DEV)
+    buf = torch.full((N * stride + offset + 64,), 512.0, dtype=w.torch_dtype, device=DEV)
     X = buf[offset: offset + N * stride].view(N, stride)[:, :P]
     X.copy_(inputs.make_state(w, DEV))
     ref = to_f64(X).copy()
@@ -102,10 +102,10 @@ def test_small_full_state(M, d, P, dtype, stride, offset, p):
     assert (ms >= 0).all()
     # padding and guard elements were never written
     whole = buf.to(torch.float32).cpu().numpy()
-    assert (whole[:offset] == 777.0).all() and (whole[offset + N * stride:] == 777.0).all()
+    assert (whole[:offset] == 512.0).all() and (whole[offset + N * stride:] == 512.0).all()
     if stride > P:
         pad = whole[offset: offset + N * stride].reshape(N, stride)[:, P:]
-        assert (pad == 777.0).all()
+        assert (pad == 512.0).all()
 
 
 def test_workload1_is_exact_global_mean():
