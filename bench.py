@@ -69,7 +69,8 @@ def main() -> int:
     ap.add_argument("--cpu-cols", type=int, default=-1,
                     help="columns of the state the CPU oracle is timed on (0 = skip, -1 = auto)")
     ap.add_argument("--no-copy-probe", action="store_true")
-    ap.add_argument("--tuning", type=str, default="", help="cols,unroll,nontemporal override for sweeps")
+    ap.add_argument("--tuning", type=str, default="", help="cols,unroll,nontemporal[,block,waves_per_cu] override for sweeps")
+    ap.add_argument("--row-pad", type=int, default=0, help="extra elements between rows (row_stride = P + pad)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -89,7 +90,7 @@ def main() -> int:
     log(f"[bench] workload {w.name}: N={w.N} (M={w.M}, d={w.d}) P={w.P} "
         f"{'f32' if w.dtype == 0 else 'bf16'} state {w.N * w.P * s / 2**30:.2f} GiB, {w.rounds} rounds/step")
     t_gen = time.time()
-    X = inputs.make_state(w, dev)
+    X = inputs.make_state(w, dev, row_stride=w.P + args.row_pad)
     torch.cuda.synchronize()
     log(f"[bench] state generated in {time.time() - t_gen:.1f}s")
 
@@ -97,8 +98,7 @@ def main() -> int:
     m = binding.Moshpit(w.N, w.P, w.M, w.d, w.dtype)
     m.bind_state(X)
     if args.tuning:
-        c, u, nt = (int(v) for v in args.tuning.split(","))
-        m.set_tuning(c, u, nt)
+        m.set_tuning(*(int(v) for v in args.tuning.split(",")))
 
     total_steps = args.warmup + args.steps
     all_masks = m.schedule_mask(sched, 0, total_steps * w.rounds)

@@ -141,16 +141,22 @@ int moshpit_schedule_mask(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0,
  * moshpit_set_tuning overrides the launch shape of the averaging kernel:
  * cols = 128-bit vectors per thread per row, unroll = rows whose loads are
  * issued before the first add; supported (cols, unroll) pairs are (1,4) (1,8)
- * (1,16) (2,2) (2,4) (2,8) (4,2) (4,4); cols = unroll = 0 restores the default
+ * (1,16) (1,32) (2,2) (2,4) (2,8) (2,16) (4,2) (4,4) (4,8); cols = unroll = 0
+ * restores the default
  * chosen from M and the dtype.  nontemporal: 1 = streaming loads/stores, 0 =
- * plain, -1 = default.  Results never depend on nontemporal; they depend on
+ * plain, -1 = default.  block = threads per block (64, 128, 256; 0 = default).
+ * waves_per_cu = resident waves per compute unit, 1..32 (0 = default); the
+ * kernel runs fastest when the row loads in flight on the whole chip stay
+ * near 16-32 MiB, so groups with many rows want few resident waves.
+ * Results never depend on nontemporal, block or waves_per_cu; they depend on
  * unroll only through the (documented, fixed) summation tree.
  *
  * moshpit_copy_probe queues a plain 128-bit copy of nbytes (multiple of 16,
  * both pointers device, 16-byte aligned) on hip_stream: the streaming ceiling
  * the averaging kernel is compared with, and the known-size kernel used to
  * calibrate HBM traffic counters. */
-int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t nontemporal);
+int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t nontemporal, int32_t block,
+                       int32_t waves_per_cu);
 int moshpit_copy_probe(void *dst_dev, const void *src_dev, int64_t nbytes, void *hip_stream);
 
 /* Wait until everything queued on the bound stream has finished. */

@@ -65,7 +65,7 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_dist_to_mean.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
     lib.moshpit_group_keys.argtypes = [vp, i64, vp]
     lib.moshpit_schedule_mask.argtypes = [vp, ctypes.POINTER(_CSchedule), i64, i32, vp]
-    lib.moshpit_set_tuning.argtypes = [vp, i32, i32, i32]
+    lib.moshpit_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.moshpit_copy_probe.argtypes = [vp, vp, i64, vp]
     lib.moshpit_sync.argtypes = [vp]
     lib.moshpit_last_error.argtypes = [vp]
@@ -192,8 +192,10 @@ class Moshpit:
         del keep
         return masks
 
-    def set_tuning(self, cols: int = 0, unroll: int = 0, nontemporal: int = -1) -> None:
-        self._check(self._lib.moshpit_set_tuning(self._h, cols, unroll, nontemporal), "set_tuning")
+    def set_tuning(self, cols: int = 0, unroll: int = 0, nontemporal: int = -1, block: int = 0,
+                   waves_per_cu: int = 0) -> None:
+        self._check(self._lib.moshpit_set_tuning(self._h, cols, unroll, nontemporal, block, waves_per_cu),
+                    "set_tuning")
 
     def sync(self) -> None:
         self._check(self._lib.moshpit_sync(self._h), "sync")

@@ -350,18 +350,25 @@ int moshpit_sync(moshpit_ctx *h)
     return MOSHPIT_OK;
 }
 
-int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t nontemporal)
+int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t nontemporal, int32_t block,
+                       int32_t waves_per_cu)
 {
     if (!h) return MOSHPIT_EINVAL;
     if (cols > 0 || unroll > 0) {
-        static const int ok[][2] = {{1, 4}, {1, 8}, {1, 16}, {2, 2}, {2, 4}, {2, 8}, {4, 2}, {4, 4}};
+        static const int ok[][2] = {{1, 4}, {1, 8}, {1, 16}, {1, 32}, {2, 2}, {2, 4}, {2, 8}, {2, 16},
+                                   {4, 2}, {4, 4}, {4, 8}};
         bool found = false;
         for (const auto &pair : ok) found = found || (pair[0] == cols && pair[1] == unroll);
         if (!found) return fail(h, MOSHPIT_EINVAL, "unsupported launch shape cols=%d unroll=%d", cols, unroll);
     }
     h->tune.cols = cols;
     h->tune.unroll = unroll;
+    if (block != 0 && block != 64 && block != 128 && block != 256)
+        return fail(h, MOSHPIT_EINVAL, "block must be 0, 64, 128 or 256");
+    if (waves_per_cu < 0 || waves_per_cu > 32) return fail(h, MOSHPIT_EINVAL, "waves_per_cu must be in [0, 32]");
     h->tune.nt = nontemporal;
+    h->tune.block = block;
+    h->tune.waves_per_cu = waves_per_cu;
     return MOSHPIT_OK;
 }
 

@@ -26,7 +26,8 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBlock = 256;
+constexpr int kMaxBlock = 256;          // threads per block: 64, 128 or 256
+constexpr int kLdsPerCu = 160 * 1024;   // gfx950: LDS bytes per compute unit
 
 __device__ __forceinline__ uint32_t bf16_bits_rne(float f)
 {
@@ -109,10 +110,10 @@ template <bool NT, typename T> __device__ __forceinline__ void store_vec(T *p, c
 // X            state, byte pointer to element (row 0, first column of this launch)
 // row_bytes    distance between rows in bytes
 // nvec         vectors of VE elements per row covered by this launch
-// tiles        ceil(nvec / (kBlock * COLS))
+// tiles        ceil(nvec / (blockDim.x * COLS))
 // work_items   (N / M) * tiles
 template <int DT, int VE, int COLS, int U, bool NT>
-__global__ __launch_bounds__(kBlock) void group_mean_kernel(char *X, int64_t row_bytes, int64_t nvec,
+__global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t row_bytes, int64_t nvec,
                                                             const uint8_t *__restrict__ alive, int32_t M,
                                                             int64_t S, int64_t tiles, int64_t work_items)
 {
@@ -120,6 +121,7 @@ __global__ __launch_bounds__(kBlock) void group_mean_kernel(char *X, int64_t row
     typedef typename V::mem_t mem_t;
     constexpr int NE = V::NE;
     const int lane = threadIdx.x & 63;
+    const int kBlock = blockDim.x;
 
     for (int64_t w = blockIdx.x; w < work_items; w += gridDim.x) {
         const int64_t g = w / tiles;
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(kBlock) void group_mean_kernel(char *X, int64_t row
         const int cnt = __popcll(live);
         if (cnt < 2) continue;                       // nothing to average: rows stay as they are
 
-        const int64_t v0 = tile * (kBlock * COLS) + threadIdx.x;
+        const int64_t v0 = tile * (static_cast<int64_t>(kBlock) * COLS) + threadIdx.x;
         bool in_row[COLS];
 #pragma unroll
         for (int c = 0; c < COLS; ++c) in_row[c] = (v0 + c * kBlock) < nvec;
@@ -200,35 +202,56 @@ __global__ __launch_bounds__(kBlock) void group_mean_kernel(char *X, int64_t row
     }
 }
 
+// The kernel uses no LDS.  The dynamic-LDS size of the launch is only a
+// throttle: a block that reserves lds bytes lets floor(160 KiB / lds) blocks
+// share a compute unit, which bounds the number of row loads in flight.
 template <int DT, int VE, int COLS, int U, bool NT>
 hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *alive, const RoundGeom &geom,
-                      hipStream_t stream)
+                      int block, int waves_per_cu, hipStream_t stream)
 {
     if (nvec <= 0) return hipSuccess;
-    const int64_t tiles = (nvec + kBlock * COLS - 1) / (kBlock * COLS);
+    const int64_t per_tile = static_cast<int64_t>(block) * COLS;
+    const int64_t tiles = (nvec + per_tile - 1) / per_tile;
     const int64_t work = (geom.N / geom.M) * tiles;
     const int64_t grid = work < 0x7fffffffLL ? work : 0x7fffffffLL;
-    group_mean_kernel<DT, VE, COLS, U, NT><<<dim3(static_cast<uint32_t>(grid)), dim3(kBlock), 0, stream>>>(
-        X, row_bytes, nvec, alive, geom.M, geom.S, tiles, work);
+    auto kernel = group_mean_kernel<DT, VE, COLS, U, NT>;
+    size_t lds = 0;
+    if (waves_per_cu > 0 && waves_per_cu < 32) {
+        int blocks_per_cu = waves_per_cu / (block / 64);
+        if (blocks_per_cu < 1) blocks_per_cu = 1;
+        lds = static_cast<size_t>(kLdsPerCu / blocks_per_cu) / 512 * 512;
+        static bool raised = false;                 // per instantiation
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    kernel<<<dim3(static_cast<uint32_t>(grid)), dim3(block), lds, stream>>>(X, row_bytes, nvec, alive, geom.M,
+                                                                            geom.S, tiles, work);
     return hipGetLastError();
 }
 
 template <int DT, int VE>
 hipError_t launch_shape(int cols, int unroll, bool nt, char *X, int64_t row_bytes, int64_t nvec,
-                        const uint8_t *alive, const RoundGeom &geom, hipStream_t stream)
+                        const uint8_t *alive, const RoundGeom &geom, int block, int wpc, hipStream_t stream)
 {
 #define MOSHPIT_CASE(C, UU)                                                                          \
     if (cols == C && unroll == UU)                                                                   \
-        return nt ? launch_one<DT, VE, C, UU, true>(X, row_bytes, nvec, alive, geom, stream)         \
-                  : launch_one<DT, VE, C, UU, false>(X, row_bytes, nvec, alive, geom, stream);
+        return nt ? launch_one<DT, VE, C, UU, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream)   \
+                  : launch_one<DT, VE, C, UU, false>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
     MOSHPIT_CASE(1, 4)
     MOSHPIT_CASE(1, 8)
     MOSHPIT_CASE(1, 16)
+    MOSHPIT_CASE(1, 32)
     MOSHPIT_CASE(2, 2)
     MOSHPIT_CASE(2, 4)
     MOSHPIT_CASE(2, 8)
+    MOSHPIT_CASE(2, 16)
     MOSHPIT_CASE(4, 2)
     MOSHPIT_CASE(4, 4)
+    MOSHPIT_CASE(4, 8)
 #undef MOSHPIT_CASE
     return hipErrorInvalidValue;
 }
@@ -245,26 +268,40 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     const int64_t nvec = aligned ? P / ve : 0;          // 128-bit part of every row
     const int64_t tail0 = nvec * ve;                    // first column of the element-wise part
 
+    // Defaults (measured on MI355X, see the sweep notes in the design document):
+    // one-wave blocks, each wave keeps about 16 KiB of row loads in flight
+    // (rows per chunk x cols x 1 KiB) and 5-6 waves share a compute unit, i.e.
+    // about 20-24 MiB in flight on the chip.  More than that and the HBM
+    // controllers see too many open pages; less and latency is not covered.
     int cols = tune.cols, unroll = tune.unroll;
     if (cols <= 0 || unroll <= 0) {
-        // aim for ~16 independent 128-bit loads per lane before the first add
-        if (geom.M >= 8) { unroll = 8; cols = dtype == 0 ? 2 : 1; }
-        else if (geom.M >= 4) { unroll = 4; cols = dtype == 0 ? 4 : 2; }
+        if (geom.M > 8) { unroll = 16; cols = 1; }
+        else if (geom.M > 4) { unroll = 8; cols = 2; }
+        else if (geom.M > 2) { unroll = 4; cols = 4; }
         else { unroll = 2; cols = 4; }
     }
-    const bool nt = tune.nt > 0;
+    const bool nt = tune.nt != 0;
+    const int block = (tune.block == 64 || tune.block == 128 || tune.block == 256) ? tune.block : 64;
+    int wpc = tune.waves_per_cu;
+    if (wpc <= 0) {
+        const int rows = geom.M < unroll ? geom.M : unroll;
+        const int kib_per_wave = rows * cols * (block / 64);
+        wpc = (dtype == 0 ? 80 : 96) / kib_per_wave * (block / 64);
+        if (wpc < 4) wpc = 4;
+        if (wpc > 32) wpc = 32;
+    }
 
     char *base = static_cast<char *>(X);
     hipError_t e = hipSuccess;
     if (nvec > 0) {
-        e = dtype == 0 ? launch_shape<0, 4>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, stream)
-                       : launch_shape<1, 8>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, stream);
+        e = dtype == 0 ? launch_shape<0, 4>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, block, wpc, stream)
+                       : launch_shape<1, 8>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, block, wpc, stream);
         if (e != hipSuccess) return e;
     }
     if (tail0 < P) {
         char *tbase = base + tail0 * esize;
-        e = dtype == 0 ? launch_one<0, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, stream)
-                       : launch_one<1, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, stream);
+        e = dtype == 0 ? launch_one<0, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream)
+                       : launch_one<1, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream);
     }
     return e;
 }
@@ -272,6 +309,7 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
 // ---- plain copy, the streaming ceiling the round kernel is measured against ----
 
 namespace {
+constexpr int kBlock = 256;
 __global__ __launch_bounds__(kBlock) void copy_probe_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
                                                             int64_t nvec)
 {

@@ -9,12 +9,15 @@ namespace moshpit {
 
 // Launch shape of the group-mean kernel.  cols = 128-bit vectors per thread per
 // row, unroll = rows whose loads are issued before the first add, nt =
-// non-temporal loads and stores.  0 / -1 mean "choose from M and the dtype".
+// non-temporal loads and stores, block = threads per block (64/128/256),
+// waves_per_cu = resident waves per compute unit (enforced through the
+// launch's LDS reservation).  0 / -1 mean "choose from M and the dtype".
 struct MeanTuning {
     int cols = 0;
     int unroll = 0;
     int nt = -1;
     int block = 0;
+    int waves_per_cu = 0;
 };
 
 // Geometry of one round: group g (0 <= g < N/M) owns rows base(g) + j*S,
