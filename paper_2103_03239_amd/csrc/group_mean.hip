@@ -148,23 +148,25 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
 #pragma unroll
             for (int e = 0; e < NE; ++e) acc[c][e] = 0.f;
 
-        uint64_t rem = live;
-        while (rem != 0) {
+        // Rows are taken in chunks of U by POSITION j (absent rows contribute an
+        // exact 0 and cost no load), so the summation order is a fixed balanced
+        // tree over the M slots whatever the mask: ((x0+x1)+(x2+x3))+... per
+        // chunk, chunks added in ascending order.
+        for (int j0 = 0; j0 < M; j0 += U) {
+            const uint64_t bits = (live >> j0) & (U >= 64 ? ~0ull : ((1ull << (U % 64)) - 1ull));
+            if (bits == 0) continue;
             mem_t buf[U][COLS];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int c = 0; c < COLS; ++c) buf[u][c] = V::zero();
-                if (rem != 0) {
-                    const int j = __builtin_ctzll(rem);
-                    rem &= rem - 1;
-                    const mem_t *src = reinterpret_cast<const mem_t *>(gbase + j * jstep);
+                if ((bits >> u) & 1ull) {
+                    const mem_t *src = reinterpret_cast<const mem_t *>(gbase + (j0 + u) * jstep);
 #pragma unroll
                     for (int c = 0; c < COLS; ++c)
                         if (in_row[c]) buf[u][c] = load_vec<NT>(src + c * kBlock);
                 }
             }
-            // fixed-shape pairwise tree over the U slots (absent slots hold 0)
 #pragma unroll
             for (int c = 0; c < COLS; ++c) {
                 float f[U][NE];
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
             mean[c] = V::narrow(acc[c]);
         }
 
-        rem = live;
+        uint64_t rem = live;
         while (rem != 0) {
             const int j = __builtin_ctzll(rem);
             rem &= rem - 1;
