@@ -76,9 +76,18 @@ typedef struct {
     const uint8_t *explicit_masks;  /* kind EXPLICIT: host, [rounds][N], 1=alive  */
 } moshpit_schedule;
 
-/* Flags of moshpit_run. */
+/* Flags of moshpit_run.
+ * MOSHPIT_RUN_FUSED allows consecutive rounds to run in one pass over HBM: a
+ * tile made of the M^F rows of an F-dimensional sub-grid (F distinct axes) and
+ * a slice of columns is closed under rounds on those axes, so it is loaded
+ * once, averaged F times on chip (any number of times when F = d) and stored
+ * once.  The state after a fused pass is bit-identical to the state after the
+ * same rounds run one by one.  Where fusion does not apply (rows not 16-byte
+ * aligned, a sub-grid too tall for on-chip memory, a single round left) the
+ * rounds run one by one. */
 enum {
-    MOSHPIT_RUN_DEFAULT = 0
+    MOSHPIT_RUN_DEFAULT = 0,
+    MOSHPIT_RUN_FUSED   = 1
 };
 
 /* Create a handle for N = M^d peers with P parameters each.
@@ -111,9 +120,11 @@ int moshpit_round_dev(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev);
  * (NULL = nobody fails).  Masks are generated on the device.
  * dist_out_host: NULL, or host array of rounds+1 doubles that receives the
  *   average distortion (see moshpit_dist_to_mean) before the first round and
- *   after every round.
+ *   after every round.  With MOSHPIT_RUN_FUSED the state between the rounds of
+ *   one pass never exists in memory; those entries are NaN.
  * round_ms_out_host: NULL, or host array of `rounds` floats that receives the
- *   GPU time of each round's averaging kernel in milliseconds.
+ *   GPU time of each round's averaging kernel in milliseconds (a fused pass's
+ *   time is split evenly over its rounds).
  * If either output array is given the call waits for the GPU before it
  * returns; otherwise it only queues the work. */
 int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedule *s,

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmoshpit.so")
 
 F32, BF16 = 0, 1
 SCHED_NONE, SCHED_IID, SCHED_REJOIN, SCHED_EXPLICIT = 0, 1, 2, 3
+RUN_DEFAULT, RUN_FUSED = 0, 1
 
 EXPORTS = [
     "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",

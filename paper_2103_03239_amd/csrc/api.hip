@@ -264,9 +264,10 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
 {
     int rc = check_ready(h);
     if (rc != MOSHPIT_OK) return rc;
-    if (flags != MOSHPIT_RUN_DEFAULT) return fail(h, MOSHPIT_EINVAL, "unknown flags 0x%x", flags);
+    if (flags & ~MOSHPIT_RUN_FUSED) return fail(h, MOSHPIT_EINVAL, "unknown flags 0x%x", flags);
     rc = check_schedule(h, s, t0, rounds);
     if (rc != MOSHPIT_OK) return rc;
+    const bool fused = (flags & MOSHPIT_RUN_FUSED) != 0;
     const bool failures = s && s->kind != MOSHPIT_SCHED_NONE;
     if (failures) {
         rc = queue_masks(h, s, t0, rounds);
@@ -282,14 +283,33 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
         rc = reserve_events(h, 2 * static_cast<size_t>(rounds));
         if (rc != MOSHPIT_OK) return rc;
     }
-    for (int32_t r = 0; r < rounds; ++r) {
-        if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * r], h->stream));
-        rc = queue_round(h, t0 + r, failures ? h->d_masks + static_cast<int64_t>(r) * h->N : nullptr);
-        if (rc != MOSHPIT_OK) return rc;
-        if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * r + 1], h->stream));
-        if (dist_out_host) {
-            rc = queue_dist(h, h->d_dist + r + 1);
+    // passes: one round each, or several when fusion is allowed and possible
+    std::vector<int32_t> pass_rounds;
+    std::vector<bool> have_dist(static_cast<size_t>(rounds) + 1, false);
+    have_dist[0] = true;
+    int32_t r = 0;
+    while (r < rounds) {
+        const size_t pass = pass_rounds.size();
+        const uint8_t *mask_r = failures ? h->d_masks + static_cast<int64_t>(r) * h->N : nullptr;
+        FusedPlan plan;
+        const bool fuse = fused && plan_fused(h->dtype, h->N, h->M, h->d, h->P, h->row_stride, h->X, t0 + r,
+                                              rounds - r, &plan);
+        if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * pass], h->stream));
+        int32_t done = 1;
+        if (fuse) {
+            HIP_TRY(h, launch_fused_rounds(h->X, h->dtype, plan, mask_r, h->stream));
+            done = plan.rounds;
+        } else {
+            rc = queue_round(h, t0 + r, mask_r);
             if (rc != MOSHPIT_OK) return rc;
+        }
+        if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * pass + 1], h->stream));
+        r += done;
+        pass_rounds.push_back(done);
+        if (dist_out_host) {
+            rc = queue_dist(h, h->d_dist + r);
+            if (rc != MOSHPIT_OK) return rc;
+            have_dist[r] = true;
         }
     }
     if (dist_out_host || round_ms_out_host) {
@@ -297,9 +317,19 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
             HIP_TRY(h, hipMemcpyAsync(dist_out_host, h->d_dist, sizeof(double) * (static_cast<size_t>(rounds) + 1),
                                       hipMemcpyDeviceToHost, h->stream));
         HIP_TRY(h, hipStreamSynchronize(h->stream));
-        if (round_ms_out_host)
-            for (int32_t r = 0; r < rounds; ++r)
-                HIP_TRY(h, hipEventElapsedTime(&round_ms_out_host[r], h->events[2 * r], h->events[2 * r + 1]));
+        if (dist_out_host)
+            for (int32_t i = 0; i <= rounds; ++i)
+                if (!have_dist[i]) dist_out_host[i] = std::nan("");
+        if (round_ms_out_host) {
+            int32_t first = 0;
+            for (size_t pass = 0; pass < pass_rounds.size(); ++pass) {
+                float ms = 0.f;
+                HIP_TRY(h, hipEventElapsedTime(&ms, h->events[2 * pass], h->events[2 * pass + 1]));
+                for (int32_t i = 0; i < pass_rounds[pass]; ++i)
+                    round_ms_out_host[first + i] = ms / static_cast<float>(pass_rounds[pass]);
+                first += pass_rounds[pass];
+            }
+        }
     }
     return MOSHPIT_OK;
 }

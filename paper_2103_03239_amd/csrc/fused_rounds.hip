@@ -1,0 +1,461 @@
+// Fused multi-round kernel for gfx950 (MI355X): several consecutive averaging
+// rounds of Moshpit All-Reduce (the loop of Alg. 1) in ONE pass over HBM.
+//
+// Columns never interact in a round (the convergence argument of App. C.2 is
+// component-wise), and the rows that interact during rounds on F distinct grid
+// axes are exactly the M^F vertices of an F-dimensional sub-grid.  So a tile
+// made of the M^F rows of one sub-grid and W columns is closed under those
+// rounds: it is read from HBM once, all fused rounds run on it in LDS, and it
+// is written back once.  When F = d the sub-grid is the whole grid and any
+// number of rounds can be fused.
+//
+// The arithmetic of a round is the one of the single-round kernel, bit for
+// bit: values live in LDS in the storage type (so bfloat16 state is rounded
+// after every round exactly as if it had gone through HBM), sums are binary32
+// over a balanced tree of 16-position blocks, blocks added in ascending order,
+// one division by the participant count.
+//
+// Schedule.  One persistent block of 1024 threads per compute unit (the tile
+// takes most of the 160 KiB of LDS).  While the rounds of tile k run in LDS the
+// 128-bit loads of tile k+1 are already in flight into registers, and the
+// stores of tile k drain while tile k+1 is being set up, so HBM time and LDS
+// arithmetic overlap.
+//
+// LDS layout (dynamic): [tile: rows x Wb bytes][2 x bitmaps: rounds x groups
+// u64][2 x row flags: rows bytes][first local row of every group per axis].
+#include "moshpit_internal.h"
+
+namespace moshpit {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 1024;
+constexpr int kLdsBytes = 160 * 1024;
+constexpr int kPrefetch = 10;         // 128-bit vectors per thread: 1024 * 10 * 16 B = 160 KiB
+
+__device__ __forceinline__ uint32_t bf16_bits_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Four consecutive columns of one row in LDS.
+template <int DT> struct Quad;
+template <> struct Quad<0> {
+    typedef float elem_t;
+    static __device__ __forceinline__ void load(const elem_t *p, float (&f)[4])
+    {
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(p);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    static __device__ __forceinline__ void store(elem_t *p, const float (&f)[4])
+    {
+        *reinterpret_cast<f32x4 *>(p) = f32x4{f[0], f[1], f[2], f[3]};
+    }
+};
+template <> struct Quad<1> {
+    typedef uint16_t elem_t;
+    static __device__ __forceinline__ void load(const elem_t *p, float (&f)[4])
+    {
+        const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(elem_t *p, const float (&f)[4])
+    {
+        *reinterpret_cast<u32x2 *>(p) = u32x2{bf16_bits_rne(f[0]) | (bf16_bits_rne(f[1]) << 16),
+                                              bf16_bits_rne(f[2]) | (bf16_bits_rne(f[3]) << 16)};
+    }
+};
+
+// global row of local row lr: base + sum_f digit_f(lr) * gstride[f]
+__device__ __forceinline__ int64_t global_row(const FusedPlan &p, int64_t base, int32_t lr)
+{
+    int64_t row = base;
+    int32_t rest = lr;
+    for (int f = 0; f < p.F; ++f) {
+        const int32_t digit = rest % p.M;
+        rest /= p.M;
+        row += digit * p.gstride[f];
+    }
+    return row;
+}
+
+struct TileRef {
+    int64_t base;          // first global row of the sub-grid
+    int64_t col0_bytes;    // first byte of the column slice within a row
+    int32_t seg_bytes;     // bytes of the slice that exist (last slice may be short)
+};
+
+__device__ __forceinline__ TileRef tile_ref(const FusedPlan &p, int64_t w)
+{
+    TileRef t;
+    const int64_t plane = w / p.tiles;
+    const int64_t ctile = w - plane * p.tiles;
+    t.base = 0;
+    int64_t rest = plane;
+    for (int o = 0; o < p.n_outer; ++o) {
+        t.base += (rest % p.M) * p.ostride[o];
+        rest /= p.M;
+    }
+    t.col0_bytes = ctile * p.Wb;
+    const int64_t left = p.row_valid_bytes - t.col0_bytes;
+    t.seg_bytes = static_cast<int32_t>(left < p.Wb ? left : p.Wb);
+    return t;
+}
+
+// Sum of TREE positions j0..j0+TREE-1 of a group column quad, as the balanced
+// tree ((x0+x1)+(x2+x3))+...; positions whose bit is clear contribute an exact 0.
+template <int DT, int TREE>
+__device__ __forceinline__ void tree_block(const typename Quad<DT>::elem_t *col, int32_t step, int32_t j0, int32_t M,
+                                           uint32_t bits, float (&out)[4])
+{
+    if constexpr (TREE > 4) {
+        // a balanced tree is the sum of its two balanced halves; one half at a
+        // time keeps the register footprint at 4 rows
+        float lo[4], hi[4];
+        tree_block<DT, TREE / 2>(col, step, j0, M, bits & ((1u << (TREE / 2)) - 1u), lo);
+        tree_block<DT, TREE / 2>(col, step, j0 + TREE / 2, M, bits >> (TREE / 2), hi);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = lo[e] + hi[e];
+    } else {
+        float f[TREE][4];
+#pragma unroll
+        for (int u = 0; u < TREE; ++u) {
+            const int32_t j = (j0 + u) < M ? (j0 + u) : (M - 1);      // never read past the group
+            Quad<DT>::load(col + j * step, f[u]);
+            const bool on = (bits >> u) & 1u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[u][e] = on ? f[u][e] : 0.f;
+        }
+#pragma unroll
+        for (int s = 1; s < TREE; s *= 2)
+#pragma unroll
+            for (int u = 0; u + s < TREE; u += 2 * s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) f[u][e] += f[u + s][e];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = f[0][e];
+    }
+}
+
+// TREE = size of the summation block actually needed: 16 for M > 8, else the
+// next power of two >= M (a 16-block padded with zeros gives the same bits).
+template <int DT, int TREE>
+__global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const uint8_t *__restrict__ masks, FusedPlan p)
+{
+    typedef Quad<DT> Q;
+    typedef typename Q::elem_t elem_t;
+    extern __shared__ __align__(16) char lds[];
+    char *tile = lds;
+    const int32_t bm_count = p.rounds * p.groups;
+    uint64_t *bitmaps0 = reinterpret_cast<uint64_t *>(lds + p.tile_bytes);
+    uint8_t *rowflag0 = reinterpret_cast<uint8_t *>(bitmaps0 + 2 * bm_count);
+    int32_t *lbase_tab = reinterpret_cast<int32_t *>(rowflag0 + 2 * p.rows_padded);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    constexpr int kWaves = kThreads / 64;
+
+    // first local row of group gl on local axis f
+    for (int32_t i = tid; i < p.F * p.groups; i += kThreads) {
+        const int32_t f = i / p.groups, gl = i - f * p.groups;
+        int32_t Sl = 1;
+        for (int q = 0; q < f; ++q) Sl *= p.M;
+        lbase_tab[i] = (gl / Sl) * Sl * p.M + (gl % Sl);
+    }
+
+    const int32_t Wv = p.Wb / 16;
+    const int32_t total_vec = p.rows * Wv;
+    const int32_t W = p.Wb / static_cast<int32_t>(sizeof(elem_t));     // columns of a full tile
+
+    // Participant bitmaps of every (round, group) of a tile and per-row "used" flags.
+    auto prepare = [&](const TileRef &t, int buf) {
+        uint64_t *bm = bitmaps0 + buf * bm_count;
+        uint8_t *flag = rowflag0 + buf * p.rows_padded;
+        for (int32_t lr = tid; lr < p.rows; lr += kThreads) flag[lr] = 0;
+        __syncthreads();
+        for (int32_t item = wave; item < bm_count; item += kWaves) {
+            const int32_t r = item / p.groups;
+            const int32_t gl = item - r * p.groups;
+            const int32_t lf = (p.local_axis0 + r) % p.F;
+            int32_t Sl = 1;
+            for (int q = 0; q < lf; ++q) Sl *= p.M;
+            const int32_t lbase = (gl / Sl) * Sl * p.M + (gl % Sl);
+            bool takes_part = false;
+            int32_t lr = 0;
+            if (lane < p.M) {
+                lr = lbase + lane * Sl;
+                takes_part = masks == nullptr ||
+                             masks[static_cast<int64_t>(r) * p.N + global_row(p, t.base, lr)] != 0;
+            }
+            const uint64_t live = __ballot(takes_part);
+            if (lane == 0) bm[item] = live;
+            if (takes_part) flag[lr] = 1;              // benign race: every writer stores 1
+        }
+        __syncthreads();
+    };
+
+    // Issue the tile's 128-bit loads into registers; returns the mask of slots in use.
+    u32x4 pre[kPrefetch];
+    auto fetch = [&](const TileRef &t, int buf) -> uint32_t {
+        const uint8_t *flag = rowflag0 + buf * p.rows_padded;
+        const int32_t seg_vec = t.seg_bytes / 16;
+        uint32_t used = 0;
+#pragma unroll
+        for (int b = 0; b < kPrefetch; ++b) {
+            const int32_t idx = tid + b * kThreads;
+            if (idx < total_vec) {
+                const int32_t lr = idx / Wv;
+                const int32_t v = idx - lr * Wv;
+                if (v < seg_vec && flag[lr]) {
+                    const char *src = X + global_row(p, t.base, lr) * p.row_bytes + t.col0_bytes + v * 16;
+                    pre[b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+                    used |= 1u << b;
+                }
+            }
+        }
+        return used;
+    };
+
+    // The fused rounds of one tile, in LDS, with the bitmaps of buffer `buf`.
+    auto compute = [&](const TileRef &t, int buf) {
+        const uint64_t *bm = bitmaps0 + buf * bm_count;
+        const int32_t cchunks = t.seg_bytes / (4 * static_cast<int32_t>(sizeof(elem_t)));
+        elem_t *T = reinterpret_cast<elem_t *>(tile);
+        const int32_t g_first = tid / cchunks, c_first = tid - g_first * cchunks;
+        const int32_t dg = kThreads / cchunks, dc = kThreads - dg * cchunks;
+        for (int32_t r = 0; r < p.rounds; ++r) {
+            const int32_t lf = (p.local_axis0 + r) % p.F;
+            int32_t Sl = 1;
+            for (int q = 0; q < lf; ++q) Sl *= p.M;
+            const int32_t step = Sl * W;
+            const int32_t *lb = lbase_tab + lf * p.groups;
+            const uint64_t *bmr = bm + r * p.groups;
+            int32_t gl = g_first, cc = c_first;
+            while (gl < p.groups) {
+                const uint64_t live = bmr[gl];
+                const int cnt = __popcll(live);
+                if (cnt >= 2) {
+                    elem_t *col = T + static_cast<int64_t>(lb[gl]) * W + cc * 4;
+                    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+                    if constexpr (TREE < 16) {
+                        float t0[4];
+                        tree_block<DT, TREE>(col, step, 0, p.M, static_cast<uint32_t>(live), t0);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[e] += t0[e];
+                    } else {
+                        for (int32_t j0 = 0; j0 < p.M; j0 += 16) {
+                            const uint32_t bits = static_cast<uint32_t>(live >> j0) & 0xffffu;
+                            if (bits == 0) continue;
+                            float t16[4];
+                            tree_block<DT, 16>(col, step, j0, p.M, bits, t16);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[e] += t16[e];
+                        }
+                    }
+                    const float k = static_cast<float>(cnt);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[e] = acc[e] / k;
+                    uint64_t rem = live;
+                    while (rem != 0) {
+                        const int j = __builtin_ctzll(rem);
+                        rem &= rem - 1;
+                        Q::store(col + j * step, acc);
+                    }
+                }
+                cc += dc;
+                gl += dg;
+                if (cc >= cchunks) { cc -= cchunks; gl += 1; }
+            }
+            __syncthreads();
+        }
+    };
+
+    // Software pipeline over the block's tiles k = 0, 1, 2, ...:
+    //   while tile k is averaged in LDS, the loads of tile k+1 are in flight into
+    //   `pre`; afterwards tile k leaves LDS for HBM and tile k+1 enters LDS from
+    //   `pre`, the loads of tile k+2 are issued, and tile k+1 is averaged while
+    //   both drain.  The mask reads of prepare() come before the stores are
+    //   issued, so waiting for them never waits for a store.
+    const int64_t stride = gridDim.x;
+    int64_t w = blockIdx.x;
+    if (w >= p.work_items) return;
+    TileRef cur = tile_ref(p, w);
+    prepare(cur, 0);
+    uint32_t used_cur = fetch(cur, 0);
+#pragma unroll
+    for (int b = 0; b < kPrefetch; ++b)
+        if (used_cur & (1u << b)) *reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(tid + b * kThreads) * 16) = pre[b];
+    __syncthreads();
+    bool has_next = w + stride < p.work_items;
+    TileRef nxt = cur;
+    uint32_t used_next = 0;
+    if (has_next) {
+        nxt = tile_ref(p, w + stride);
+        prepare(nxt, 1);
+        used_next = fetch(nxt, 1);
+    }
+    int buf = 0;
+
+    while (true) {
+        compute(cur, buf);
+
+        const bool has_next2 = has_next && (w + 2 * stride < p.work_items);
+        TileRef nn = nxt;
+        if (has_next2) {
+            nn = tile_ref(p, w + 2 * stride);
+            prepare(nn, buf);                  // tile k's bitmaps are no longer needed
+        }
+        // Each thread owns the same tile slots for every tile, so it can swap
+        // tile k out of LDS and tile k+1 in, slot by slot, without a barrier.
+#pragma unroll
+        for (int b = 0; b < kPrefetch; ++b) {
+            u32x4 *slot = reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(tid + b * kThreads) * 16);
+            const bool out_b = used_cur & (1u << b);
+            u32x4 val;
+            if (out_b) val = *slot;
+            if (has_next && (used_next & (1u << b))) *slot = pre[b];
+            if (out_b) {
+                const int32_t idx = tid + b * kThreads;
+                const int32_t lr = idx / Wv;
+                const int32_t v = idx - lr * Wv;
+                char *dst = X + global_row(p, cur.base, lr) * p.row_bytes + cur.col0_bytes + v * 16;
+                __builtin_nontemporal_store(val, reinterpret_cast<u32x4 *>(dst));
+            }
+        }
+        if (!has_next) break;
+        __syncthreads();
+        uint32_t used_nn = 0;
+        if (has_next2) used_nn = fetch(nn, buf);
+        w += stride;
+        cur = nxt;
+        used_cur = used_next;
+        nxt = nn;
+        used_next = used_nn;
+        has_next = has_next2;
+        buf ^= 1;
+    }
+}
+
+int tree_size(int32_t M) { return M > 8 ? 16 : M > 4 ? 8 : M > 2 ? 4 : 2; }
+
+int64_t fixed_lds(int64_t rounds, int64_t rows, int64_t groups, int64_t F)
+{
+    const int64_t rows_padded = (rows + 15) / 16 * 16;
+    return 2 * rounds * groups * 8 + 2 * rows_padded + F * groups * 4 + 64;
+}
+
+}  // namespace
+
+bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t row_stride, const void *X,
+                int64_t t0, int32_t rounds_wanted, FusedPlan *out)
+{
+    const int64_t esize = dtype == 0 ? 4 : 2;
+    const int64_t row_bytes = row_stride * esize;
+    const int64_t valid = P * esize;
+    if (rounds_wanted < 2) return false;
+    if (reinterpret_cast<uintptr_t>(X) % 16 != 0 || row_bytes % 16 != 0 || valid % 16 != 0) return false;
+
+    // widest sub-grid (most axes) whose rows still get >= 128 bytes each
+    int F = 1;
+    int64_t rows = M;
+    while (F < d && F < rounds_wanted && F < kFusedMaxAxes) {
+        const int64_t next = rows * M;
+        const int64_t min_rounds = (F + 1 == d) ? 2 : (F + 1);
+        if (next * 128 + fixed_lds(min_rounds, next, next / M, F + 1) > kLdsBytes) break;
+        rows = next;
+        ++F;
+    }
+    if (F < 2) return false;                    // one axis per pass is the single-round kernel
+
+    FusedPlan p{};
+    p.N = N; p.M = M; p.F = F;
+    p.rows = static_cast<int32_t>(rows);
+    p.rows_padded = static_cast<int32_t>((rows + 15) / 16 * 16);
+    p.groups = static_cast<int32_t>(rows / M);
+    p.row_bytes = row_bytes;
+    p.row_valid_bytes = valid;
+    int32_t rounds = rounds_wanted;
+    if (F < d) {
+        rounds = F;                              // the tile is closed under exactly these F axes
+        p.local_axis0 = 0;
+        for (int f = 0; f < F; ++f) {
+            int64_t S = 1;
+            for (int64_t q = 0; q < (t0 + f) % d; ++q) S *= M;
+            p.gstride[f] = S;
+        }
+        // outer axes: every grid axis not among the fused ones, ascending
+        p.n_outer = 0;
+        for (int a = 0; a < d; ++a) {
+            bool inside = false;
+            for (int f = 0; f < F; ++f) inside = inside || ((t0 + f) % d == a);
+            if (inside) continue;
+            int64_t S = 1;
+            for (int q = 0; q < a; ++q) S *= M;
+            p.ostride[p.n_outer++] = S;
+        }
+    } else {
+        // whole grid in the tile: local axis f is grid axis f, any number of rounds
+        p.local_axis0 = static_cast<int32_t>(t0 % d);
+        int64_t S = 1;
+        for (int f = 0; f < F; ++f) { p.gstride[f] = S; S *= M; }
+        p.n_outer = 0;
+        const int64_t max_rounds = 8192 / (static_cast<int64_t>(p.groups) * 8);    // <= 16 KiB of bitmaps
+        if (rounds > max_rounds) rounds = static_cast<int32_t>(max_rounds);
+        if (rounds < 2) return false;
+    }
+    p.rounds = rounds;
+    const int64_t fixed = fixed_lds(rounds, rows, p.groups, F);
+    int64_t wb = (kLdsBytes - fixed) / rows;
+    wb = wb >= 128 ? wb / 128 * 128 : 0;
+    if (wb < 128) return false;
+    if (wb > valid) wb = valid;                  // a multiple of 16 (checked above)
+    if (rows * (wb / 16) > static_cast<int64_t>(kThreads) * kPrefetch) return false;
+    p.Wb = static_cast<int32_t>(wb);
+    p.tile_bytes = static_cast<int32_t>(rows * wb);
+    p.lds_bytes = static_cast<int32_t>(p.tile_bytes + fixed);
+    p.tiles = (valid + wb - 1) / wb;
+    p.planes = N / rows;
+    p.work_items = p.planes * p.tiles;
+    *out = p;
+    return true;
+}
+
+hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const uint8_t *masks, hipStream_t stream)
+{
+    typedef void (*kernel_t)(char *, const uint8_t *, FusedPlan);
+    static const kernel_t table[2][4] = {
+        {fused_rounds_kernel<0, 2>, fused_rounds_kernel<0, 4>, fused_rounds_kernel<0, 8>, fused_rounds_kernel<0, 16>},
+        {fused_rounds_kernel<1, 2>, fused_rounds_kernel<1, 4>, fused_rounds_kernel<1, 8>, fused_rounds_kernel<1, 16>}};
+    static bool raised[2][4] = {{false, false, false, false}, {false, false, false, false}};
+    static int compute_units = 0;
+    const int tree = tree_size(plan.M);
+    const int ti = tree == 2 ? 0 : tree == 4 ? 1 : tree == 8 ? 2 : 3;
+    const kernel_t kernel = table[dtype][ti];
+    if (!raised[dtype][ti]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        raised[dtype][ti] = true;
+    }
+    if (compute_units == 0) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&compute_units, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (compute_units <= 0) compute_units = 256;
+    }
+    // persistent: one block per compute unit walks the tiles
+    const int64_t grid = plan.work_items < compute_units ? plan.work_items : compute_units;
+    kernel<<<dim3(static_cast<uint32_t>(grid)), dim3(kThreads), plan.lds_bytes, stream>>>(static_cast<char *>(X), masks,
+                                                                                         plan);
+    return hipGetLastError();
+}
+
+}  // namespace moshpit

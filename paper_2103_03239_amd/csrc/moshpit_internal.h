@@ -49,6 +49,34 @@ hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down
 // Queue the group-key kernel: keys[i] (device, N int32) for axis a, S = M^a.
 hipError_t launch_group_keys(int64_t N, int32_t M, int64_t S, int32_t *keys, hipStream_t stream);
 
+// Plan of one fused pass: rounds t0..t0+rounds-1 run on tiles of `rows` = M^F
+// rows (one F-dimensional sub-grid) x Wb bytes that stay in LDS.
+constexpr int kFusedMaxAxes = 12;
+struct FusedPlan {
+    int64_t N;
+    int32_t M, F;
+    int32_t rows, groups;          // M^F rows per tile, rows / M groups per round
+    int32_t rows_padded;           // rows rounded up to a multiple of 16
+    int32_t rounds;                // rounds fused by this pass
+    int32_t local_axis0;           // tile-local axis of the first round
+    int32_t n_outer;               // grid axes outside the tile
+    int32_t Wb, tile_bytes, lds_bytes;
+    int64_t row_bytes, row_valid_bytes;
+    int64_t tiles, planes, work_items;
+    int64_t gstride[kFusedMaxAxes];   // global row stride of tile-local axis f
+    int64_t ostride[40];              // global row strides of the outer axes
+};
+
+// Decide whether rounds starting at t0 (at most rounds_wanted) can be fused
+// for this state, and how.  false = use the single-round kernel.
+bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t row_stride, const void *X,
+                int64_t t0, int32_t rounds_wanted, FusedPlan *out);
+
+// Queue one fused pass.  masks: device, [plan.rounds][N] for the pass's
+// rounds, or nullptr (all peers take part).
+hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const uint8_t *masks,
+                               hipStream_t stream);
+
 // Queue a plain 128-bit copy of nbytes (multiple of 16) from src to dst.
 hipError_t launch_copy_probe(void *dst, const void *src, int64_t nbytes, hipStream_t stream);
 

@@ -249,3 +249,73 @@ def test_full_size_workload(cfg):
     assert abs(sub - want_sub) <= 10 * TOL[w.dtype] * want_sub + dist_floor(len(cols), w.dtype, rms0)
     if w.kind == 0:
         assert dist[-1] <= dist_floor(w.P, w.dtype, rms0)
+
+
+# --------------------------------------------------------------------------
+# fused multi-round passes
+# --------------------------------------------------------------------------
+
+FUSED = [
+    # M, d, P, dtype, p, t0, rounds
+    (4, 2, 65_536, 0, 0.0, 0, 2),        # workload 1: whole 4x4 grid in one tile
+    (16, 2, 5_000, 0, 0.05, 0, 10),      # 256 rows, ragged last column tile, 5 sweeps in one pass
+    (4, 3, 10_000, 0, 0.1, 0, 6),        # 64 rows, d = 3, whole grid
+    (32, 2, 4_100, 0, 0.2, 0, 8),        # 1024 rows x 128-byte segments
+    (32, 2, 4_100, 0, 0.2, 3, 5),        # start on the second axis, odd number of rounds
+    (16, 3, 2_056, 1, 0.1, 0, 12),       # bf16, 4096 peers: planes of 256 rows, 2 rounds per pass
+    (16, 3, 2_056, 1, 0.1, 2, 7),        # plane that wraps around (axes 2 and 0), leftover single round
+    (16, 3, 1_000, 0, 0.3, 1, 2),        # fewer rounds than axes
+    (3, 3, 780, 0, 0.25, 0, 9),          # M not a power of two
+    (2, 6, 1_032, 1, 0.3, 4, 13),        # M = 2, six axes in one tile
+    (64, 1, 2_048, 0, 0.1, 0, 3),        # one axis only: nothing to fuse, falls back to single rounds
+    (8, 2, 12, 0, 0.2, 0, 4),            # rows narrower than a tile
+    (7, 2, 20_000, 1, 0.15, 0, 4),
+]
+
+
+@pytest.mark.parametrize("M,d,P,dtype,p,t0,rounds", FUSED)
+def test_fused_equals_single_rounds_and_oracle(M, d, P, dtype, p, t0, rounds):
+    N = M ** d
+    w = inputs.Workload(f"fused-{M}-{d}-{P}", N, M, d, P, dtype, "peer_offset",
+                        inputs.KIND_REJOIN if p > 0 else inputs.KIND_NONE, p, 2, rounds, 17 + P, 99 + M)
+    say(f"case {w} t0={t0}")
+    A = inputs.make_state(w, DEV)
+    B = A.clone()
+    ref = to_f64(A).copy()
+    masks = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, N, t0, rounds)
+    dist_ref = orc.run(ref, M, d, t0, rounds, masks, want_dist=True)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(A)
+        dist_a, _ = m.run(t0, rounds, sched_of(w), want_dist=True)
+        m.bind_state(B)
+        dist_b, ms = m.run(t0, rounds, sched_of(w), want_dist=True, want_times=True, flags=binding.RUN_FUSED)
+    assert torch.equal(A, B), "fused pass differs from single rounds"
+    assert_state_close(to_f64(B), ref, TOL[dtype], w.name)
+    have = ~np.isnan(dist_b)
+    assert have[0] and have[-1]
+    assert np.array_equal(dist_b[have], dist_a[have])
+    assert_dist_close(dist_b[have], dist_ref[have], TOL[dtype], dist_floor(P, dtype, 1.0), w.name)
+    assert (ms >= 0).all()
+    if d >= 2 and rounds >= 2 and M ** 2 * 128 <= 150_000:
+        assert (~have).any(), "expected at least one fused pass"
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_fused_full_size_matches_single_rounds(cfg):
+    """Full-size workloads: the fused path reproduces the single-round path bit for bit."""
+    w = inputs.CONFIGS[cfg]
+    say(f"fused full-size {w.name}")
+    A = inputs.make_state(w, DEV)
+    cols = torch.from_numpy(sample_columns(w.P, 2048, seed=50 + cfg)).to(DEV)
+    with binding.Moshpit(w.N, w.P, w.M, w.d, w.dtype) as m:
+        m.bind_state(A)
+        _, ms_a = m.run(0, w.rounds, sched_of(w), want_times=True)
+        a_cols = A.index_select(1, cols).clone()
+        a_sum = A.sum(dim=0, dtype=torch.float64)
+        del A
+        B = inputs.make_state(w, DEV)
+        m.bind_state(B)
+        _, ms_b = m.run(0, w.rounds, sched_of(w), want_times=True, flags=binding.RUN_FUSED)
+    say(f"  single rounds {ms_a.sum():.3f} ms, fused {ms_b.sum():.3f} ms")
+    assert torch.equal(B.index_select(1, cols), a_cols)
+    assert torch.equal(B.sum(dim=0, dtype=torch.float64), a_sum)
