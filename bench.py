@@ -192,7 +192,7 @@ def main() -> int:
                "rounds_per_s_full_width": round(cpu_steps * w.rounds / cpu_s * cpu_cols / w.P, 4)}
         log(f"[bench] cpu oracle: {cpu['value']} GB/s on {threads} threads ({cpu_s:.1f}s, {cpu_steps} steps)")
 
-    traffic = read_traffic(os.path.join(ROOT, "profiles", f"group_mean_cfg{args.config}_traffic.txt"))
+    traffic = read_traffic(os.path.join(ROOT, "profiles", f"group_mean_cfg{args.config}.txt"))
     out = {
         "metric": METRIC,
         "value": round(value, 2),
