@@ -22,7 +22,8 @@
 // arithmetic overlap.
 //
 // LDS layout (dynamic): [tile: rows x Wb bytes][2 x bitmaps: rounds x groups
-// u64][2 x row flags: rows bytes][first local row of every group per axis].
+// u64][byte offset of every local row][2 x row flags: rows bytes][first local
+// row of every group per axis].
 #include "moshpit_internal.h"
 
 namespace moshpit {
@@ -43,9 +44,10 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
-// Four consecutive columns of one row in LDS.
-template <int DT> struct Quad;
-template <> struct Quad<0> {
+// CV consecutive columns of one row in LDS, widened to binary32.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+template <int DT, int CV> struct Cols;
+template <> struct Cols<0, 4> {
     typedef float elem_t;
     static __device__ __forceinline__ void load(const elem_t *p, float (&f)[4])
     {
@@ -57,7 +59,24 @@ template <> struct Quad<0> {
         *reinterpret_cast<f32x4 *>(p) = f32x4{f[0], f[1], f[2], f[3]};
     }
 };
-template <> struct Quad<1> {
+template <> struct Cols<0, 2> {
+    typedef float elem_t;
+    static __device__ __forceinline__ void load(const elem_t *p, float (&f)[2])
+    {
+        const f32x2 v = *reinterpret_cast<const f32x2 *>(p);
+        f[0] = v.x; f[1] = v.y;
+    }
+    static __device__ __forceinline__ void store(elem_t *p, const float (&f)[2])
+    {
+        *reinterpret_cast<f32x2 *>(p) = f32x2{f[0], f[1]};
+    }
+};
+template <> struct Cols<0, 1> {
+    typedef float elem_t;
+    static __device__ __forceinline__ void load(const elem_t *p, float (&f)[1]) { f[0] = *p; }
+    static __device__ __forceinline__ void store(elem_t *p, const float (&f)[1]) { *p = f[0]; }
+};
+template <> struct Cols<1, 4> {
     typedef uint16_t elem_t;
     static __device__ __forceinline__ void load(const elem_t *p, float (&f)[4])
     {
@@ -69,6 +88,29 @@ template <> struct Quad<1> {
     {
         *reinterpret_cast<u32x2 *>(p) = u32x2{bf16_bits_rne(f[0]) | (bf16_bits_rne(f[1]) << 16),
                                               bf16_bits_rne(f[2]) | (bf16_bits_rne(f[3]) << 16)};
+    }
+};
+template <> struct Cols<1, 2> {
+    typedef uint16_t elem_t;
+    static __device__ __forceinline__ void load(const elem_t *p, float (&f)[2])
+    {
+        const uint32_t v = *reinterpret_cast<const uint32_t *>(p);
+        f[0] = __uint_as_float(v << 16); f[1] = __uint_as_float(v & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(elem_t *p, const float (&f)[2])
+    {
+        *reinterpret_cast<uint32_t *>(p) = bf16_bits_rne(f[0]) | (bf16_bits_rne(f[1]) << 16);
+    }
+};
+template <> struct Cols<1, 1> {
+    typedef uint16_t elem_t;
+    static __device__ __forceinline__ void load(const elem_t *p, float (&f)[1])
+    {
+        f[0] = __uint_as_float(static_cast<uint32_t>(*p) << 16);
+    }
+    static __device__ __forceinline__ void store(elem_t *p, const float (&f)[1])
+    {
+        *p = static_cast<uint16_t>(bf16_bits_rne(f[0]));
     }
 };
 
@@ -86,6 +128,7 @@ __device__ __forceinline__ int64_t global_row(const FusedPlan &p, int64_t base, 
 }
 
 struct TileRef {
+    int64_t plane;         // which sub-grid
     int64_t base;          // first global row of the sub-grid
     int64_t col0_bytes;    // first byte of the column slice within a row
     int32_t seg_bytes;     // bytes of the slice that exist (last slice may be short)
@@ -96,6 +139,7 @@ __device__ __forceinline__ TileRef tile_ref(const FusedPlan &p, int64_t w)
     TileRef t;
     const int64_t plane = w / p.tiles;
     const int64_t ctile = w - plane * p.tiles;
+    t.plane = plane;
     t.base = 0;
     int64_t rest = plane;
     for (int o = 0; o < p.n_outer; ++o) {
@@ -108,59 +152,68 @@ __device__ __forceinline__ TileRef tile_ref(const FusedPlan &p, int64_t w)
     return t;
 }
 
-// Sum of TREE positions j0..j0+TREE-1 of a group column quad, as the balanced
-// tree ((x0+x1)+(x2+x3))+...; positions whose bit is clear contribute an exact 0.
-template <int DT, int TREE>
-__device__ __forceinline__ void tree_block(const typename Quad<DT>::elem_t *col, int32_t step, int32_t j0, int32_t M,
-                                           uint32_t bits, float (&out)[4])
+// Sum of TREE positions j0..j0+TREE-1 of CV columns of a group, as the balanced
+// tree ((x0+x1)+(x2+x3))+...; positions whose bit is clear contribute an exact
+// 0.  Blocks of up to FLAT positions are read at once; larger trees are the sum
+// of their two balanced halves, which bounds the register footprint.
+template <int DT, int CV, int TREE, int FLAT>
+__device__ __forceinline__ void tree_block(const typename Cols<DT, CV>::elem_t *col, int32_t step, int32_t j0,
+                                           int32_t M, uint32_t bits, float (&out)[CV])
 {
-    if constexpr (TREE > 4) {
-        // a balanced tree is the sum of its two balanced halves; one half at a
-        // time keeps the register footprint at 4 rows
-        float lo[4], hi[4];
-        tree_block<DT, TREE / 2>(col, step, j0, M, bits & ((1u << (TREE / 2)) - 1u), lo);
-        tree_block<DT, TREE / 2>(col, step, j0 + TREE / 2, M, bits >> (TREE / 2), hi);
+    if constexpr (TREE > FLAT) {
+        float lo[CV], hi[CV];
+        tree_block<DT, CV, TREE / 2, FLAT>(col, step, j0, M, bits & ((1u << (TREE / 2)) - 1u), lo);
+        tree_block<DT, CV, TREE / 2, FLAT>(col, step, j0 + TREE / 2, M, bits >> (TREE / 2), hi);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) out[e] = lo[e] + hi[e];
+        for (int e = 0; e < CV; ++e) out[e] = lo[e] + hi[e];
     } else {
-        float f[TREE][4];
+        float f[TREE][CV];
 #pragma unroll
         for (int u = 0; u < TREE; ++u) {
             const int32_t j = (j0 + u) < M ? (j0 + u) : (M - 1);      // never read past the group
-            Quad<DT>::load(col + j * step, f[u]);
+            Cols<DT, CV>::load(col + j * step, f[u]);
             const bool on = (bits >> u) & 1u;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) f[u][e] = on ? f[u][e] : 0.f;
+            for (int e = 0; e < CV; ++e) f[u][e] = on ? f[u][e] : 0.f;
         }
 #pragma unroll
         for (int s = 1; s < TREE; s *= 2)
 #pragma unroll
             for (int u = 0; u + s < TREE; u += 2 * s)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) f[u][e] += f[u + s][e];
+                for (int e = 0; e < CV; ++e) f[u][e] += f[u + s][e];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) out[e] = f[0][e];
+        for (int e = 0; e < CV; ++e) out[e] = f[0][e];
     }
 }
 
 // TREE = size of the summation block actually needed: 16 for M > 8, else the
 // next power of two >= M (a 16-block padded with zeros gives the same bits).
-template <int DT, int TREE>
+// Value of the lane whose index differs in bit 0 (CTRL 0xB1) or bit 1 (CTRL
+// 0x4E) within each group of four lanes (DPP quad_perm).
+template <int CTRL> __device__ __forceinline__ float quad_xor(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+// CV = columns one thread averages at a time; SPLIT = adjacent lanes that share
+// the positions of one group (chosen so that every thread has work even when
+// the tile is narrow).
+template <int DT, int TREE, int CV, int SPLIT>
 __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const uint8_t *__restrict__ masks, FusedPlan p)
 {
-    typedef Quad<DT> Q;
+    typedef Cols<DT, CV> Q;
     typedef typename Q::elem_t elem_t;
+    constexpr int FLAT = 16 / CV;
     extern __shared__ __align__(16) char lds[];
     char *tile = lds;
     const int32_t bm_count = p.rounds * p.groups;
     uint64_t *bitmaps0 = reinterpret_cast<uint64_t *>(lds + p.tile_bytes);
-    uint8_t *rowflag0 = reinterpret_cast<uint8_t *>(bitmaps0 + 2 * bm_count);
+    int64_t *rowoff = reinterpret_cast<int64_t *>(bitmaps0 + 2 * bm_count);      // byte offset of local row lr
+    uint8_t *rowflag0 = reinterpret_cast<uint8_t *>(rowoff + p.rows_padded);
     int32_t *lbase_tab = reinterpret_cast<int32_t *>(rowflag0 + 2 * p.rows_padded);
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    constexpr int kWaves = kThreads / 64;
 
     // first local row of group gl on local axis f
     for (int32_t i = tid; i < p.F * p.groups; i += kThreads) {
@@ -169,56 +222,84 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
         for (int q = 0; q < f; ++q) Sl *= p.M;
         lbase_tab[i] = (gl / Sl) * Sl * p.M + (gl % Sl);
     }
+    for (int32_t lr = tid; lr < p.rows; lr += kThreads) rowoff[lr] = global_row(p, 0, lr) * p.row_bytes;
 
     const int32_t Wv = p.Wb / 16;
     const int32_t total_vec = p.rows * Wv;
     const int32_t W = p.Wb / static_cast<int32_t>(sizeof(elem_t));     // columns of a full tile
 
-    // Participant bitmaps of every (round, group) of a tile and per-row "used" flags.
+    // Participant bitmaps of every (round, group) of a sub-grid and per-row
+    // "used" flags.  They depend on the sub-grid only, not on the column slice,
+    // so a buffer is rebuilt only when the block moves to another sub-grid.
+    // One thread per (round, row): independent byte loads, bits merged with LDS
+    // atomics.
+    int64_t tag[2] = {-1, -1};
     auto prepare = [&](const TileRef &t, int buf) {
-        uint64_t *bm = bitmaps0 + buf * bm_count;
+        if (tag[buf] == t.plane) return;
+        tag[buf] = t.plane;
+        unsigned long long *bm = reinterpret_cast<unsigned long long *>(bitmaps0 + buf * bm_count);
         uint8_t *flag = rowflag0 + buf * p.rows_padded;
+        for (int32_t i = tid; i < bm_count; i += kThreads) bm[i] = 0ull;
         for (int32_t lr = tid; lr < p.rows; lr += kThreads) flag[lr] = 0;
         __syncthreads();
-        for (int32_t item = wave; item < bm_count; item += kWaves) {
-            const int32_t r = item / p.groups;
-            const int32_t gl = item - r * p.groups;
-            const int32_t lf = (p.local_axis0 + r) % p.F;
-            int32_t Sl = 1;
-            for (int q = 0; q < lf; ++q) Sl *= p.M;
-            const int32_t lbase = (gl / Sl) * Sl * p.M + (gl % Sl);
-            bool takes_part = false;
-            int32_t lr = 0;
-            if (lane < p.M) {
-                lr = lbase + lane * Sl;
-                takes_part = masks == nullptr ||
-                             masks[static_cast<int64_t>(r) * p.N + global_row(p, t.base, lr)] != 0;
+        const int32_t pairs = p.rounds * p.rows;
+        constexpr int kB = 8;
+        for (int32_t i0 = tid; i0 < pairs; i0 += kThreads * kB) {
+            uint8_t a[kB];
+#pragma unroll
+            for (int b = 0; b < kB; ++b) {
+                const int32_t i = i0 + b * kThreads;
+                a[b] = 0;
+                if (i < pairs) {
+                    const int32_t r = i / p.rows;
+                    const int32_t lr = i - r * p.rows;
+                    a[b] = masks == nullptr ? 1 : masks[static_cast<int64_t>(r) * p.N + global_row(p, t.base, lr)];
+                }
             }
-            const uint64_t live = __ballot(takes_part);
-            if (lane == 0) bm[item] = live;
-            if (takes_part) flag[lr] = 1;              // benign race: every writer stores 1
+#pragma unroll
+            for (int b = 0; b < kB; ++b) {
+                const int32_t i = i0 + b * kThreads;
+                if (i < pairs && a[b] != 0) {
+                    const int32_t r = i / p.rows;
+                    const int32_t lr = i - r * p.rows;
+                    const int32_t lf = (p.local_axis0 + r) % p.F;
+                    int32_t Sl = 1;
+                    for (int q = 0; q < lf; ++q) Sl *= p.M;
+                    const int32_t j = (lr / Sl) % p.M;
+                    const int32_t gl = (lr / (Sl * p.M)) * Sl + lr % Sl;
+                    atomicOr(&bm[r * p.groups + gl], 1ull << j);
+                    flag[lr] = 1;                      // benign race: every writer stores 1
+                }
+            }
         }
         __syncthreads();
     };
+
+    // Slot b of a thread is vector idx = tid + b * kThreads of the tile, i.e.
+    // local row idx / Wv, vector idx % Wv; walked incrementally.  The opaque
+    // copy of tid keeps this index arithmetic inside the tile loop instead of
+    // having all of it hoisted into registers that live across the rounds.
+    const int32_t slot_dq = kThreads / Wv, slot_dr = kThreads - slot_dq * Wv;
 
     // Issue the tile's 128-bit loads into registers; returns the mask of slots in use.
     u32x4 pre[kPrefetch];
     auto fetch = [&](const TileRef &t, int buf) -> uint32_t {
         const uint8_t *flag = rowflag0 + buf * p.rows_padded;
         const int32_t seg_vec = t.seg_bytes / 16;
+        const char *origin = X + t.base * p.row_bytes + t.col0_bytes;
+        int32_t t_ = tid;
+        asm volatile("" : "+v"(t_));
+        int32_t lr = t_ / Wv, v = t_ - lr * Wv;
         uint32_t used = 0;
 #pragma unroll
         for (int b = 0; b < kPrefetch; ++b) {
-            const int32_t idx = tid + b * kThreads;
-            if (idx < total_vec) {
-                const int32_t lr = idx / Wv;
-                const int32_t v = idx - lr * Wv;
-                if (v < seg_vec && flag[lr]) {
-                    const char *src = X + global_row(p, t.base, lr) * p.row_bytes + t.col0_bytes + v * 16;
-                    pre[b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
-                    used |= 1u << b;
-                }
+            if (lr < p.rows && v < seg_vec && flag[lr]) {
+                pre[b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(origin + rowoff[lr] + v * 16));
+                used |= 1u << b;
             }
+            v += slot_dr;
+            lr += slot_dq;
+            if (v >= Wv) { v -= Wv; lr += 1; }
         }
         return used;
     };
@@ -226,10 +307,15 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
     // The fused rounds of one tile, in LDS, with the bitmaps of buffer `buf`.
     auto compute = [&](const TileRef &t, int buf) {
         const uint64_t *bm = bitmaps0 + buf * bm_count;
-        const int32_t cchunks = t.seg_bytes / (4 * static_cast<int32_t>(sizeof(elem_t)));
+        const int32_t cchunks = t.seg_bytes / (CV * static_cast<int32_t>(sizeof(elem_t)));
         elem_t *T = reinterpret_cast<elem_t *>(tile);
-        const int32_t g_first = tid / cchunks, c_first = tid - g_first * cchunks;
-        const int32_t dg = kThreads / cchunks, dc = kThreads - dg * cchunks;
+        // SPLIT adjacent lanes share one (group, column chunk) item and take
+        // SPLIT equal parts of its positions
+        constexpr int kItemThreads = kThreads / SPLIT;
+        const int32_t sub = tid & (SPLIT - 1);
+        const int32_t it0 = tid / SPLIT;
+        const int32_t g_first = it0 / cchunks, c_first = it0 - g_first * cchunks;
+        const int32_t dg = kItemThreads / cchunks, dc = kItemThreads - dg * cchunks;
         for (int32_t r = 0; r < p.rounds; ++r) {
             const int32_t lf = (p.local_axis0 + r) % p.F;
             int32_t Sl = 1;
@@ -242,27 +328,48 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
                 const uint64_t live = bmr[gl];
                 const int cnt = __popcll(live);
                 if (cnt >= 2) {
-                    elem_t *col = T + static_cast<int64_t>(lb[gl]) * W + cc * 4;
-                    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-                    if constexpr (TREE < 16) {
-                        float t0[4];
-                        tree_block<DT, TREE>(col, step, 0, p.M, static_cast<uint32_t>(live), t0);
+                    elem_t *col = T + static_cast<int64_t>(lb[gl]) * W + cc * CV;
+                    float acc[CV];
+                    uint64_t mine = live;              // positions this thread writes back
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[e] += t0[e];
+                    for (int e = 0; e < CV; ++e) acc[e] = 0.f;
+                    if constexpr (SPLIT > 1) {
+                        // M <= 32 here: one or two 16-position blocks, cut into SPLIT
+                        // balanced sub-trees of 4, 8 or 16 positions; the xor butterfly
+                        // over the SPLIT lanes adds them in the order of the full tree.
+                        const int32_t per = (p.M > 16 ? 32 : 16) / SPLIT;
+                        const int32_t j0 = sub * per;
+                        const uint32_t bits = static_cast<uint32_t>(live >> j0) & ((1u << per) - 1u);
+                        mine = static_cast<uint64_t>(bits) << j0;
+                        float part[CV];
+                        if (per == 16) tree_block<DT, CV, 16, FLAT>(col, step, j0, p.M, bits, part);
+                        else if (per == 8) tree_block<DT, CV, 8, FLAT>(col, step, j0, p.M, bits, part);
+                        else tree_block<DT, CV, 4, FLAT>(col, step, j0, p.M, bits, part);
+#pragma unroll
+                        for (int e = 0; e < CV; ++e) {
+                            part[e] += quad_xor<0xB1>(part[e]);                       // lane ^ 1
+                            if constexpr (SPLIT > 2) part[e] += quad_xor<0x4E>(part[e]);   // lane ^ 2
+                            acc[e] += part[e];
+                        }
+                    } else if constexpr (TREE < 16) {
+                        float t0[CV];
+                        tree_block<DT, CV, TREE, FLAT>(col, step, 0, p.M, static_cast<uint32_t>(live), t0);
+#pragma unroll
+                        for (int e = 0; e < CV; ++e) acc[e] += t0[e];
                     } else {
                         for (int32_t j0 = 0; j0 < p.M; j0 += 16) {
                             const uint32_t bits = static_cast<uint32_t>(live >> j0) & 0xffffu;
                             if (bits == 0) continue;
-                            float t16[4];
-                            tree_block<DT, 16>(col, step, j0, p.M, bits, t16);
+                            float t16[CV];
+                            tree_block<DT, CV, 16, FLAT>(col, step, j0, p.M, bits, t16);
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[e] += t16[e];
+                            for (int e = 0; e < CV; ++e) acc[e] += t16[e];
                         }
                     }
                     const float k = static_cast<float>(cnt);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[e] = acc[e] / k;
-                    uint64_t rem = live;
+                    for (int e = 0; e < CV; ++e) acc[e] = acc[e] / k;
+                    uint64_t rem = mine;
                     while (rem != 0) {
                         const int j = __builtin_ctzll(rem);
                         rem &= rem - 1;
@@ -287,59 +394,79 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
     int64_t w = blockIdx.x;
     if (w >= p.work_items) return;
     TileRef cur = tile_ref(p, w);
-    prepare(cur, 0);
-    uint32_t used_cur = fetch(cur, 0);
+    int buf_cur = 0;
+    prepare(cur, buf_cur);
+    uint32_t used_cur = fetch(cur, buf_cur);
 #pragma unroll
     for (int b = 0; b < kPrefetch; ++b)
         if (used_cur & (1u << b)) *reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(tid + b * kThreads) * 16) = pre[b];
     __syncthreads();
     bool has_next = w + stride < p.work_items;
     TileRef nxt = cur;
+    int buf_next = buf_cur;
     uint32_t used_next = 0;
     if (has_next) {
         nxt = tile_ref(p, w + stride);
-        prepare(nxt, 1);
-        used_next = fetch(nxt, 1);
+        buf_next = nxt.plane == cur.plane ? buf_cur : buf_cur ^ 1;
+        prepare(nxt, buf_next);
+        used_next = fetch(nxt, buf_next);
     }
-    int buf = 0;
 
     while (true) {
-        compute(cur, buf);
+        compute(cur, buf_cur);
 
         const bool has_next2 = has_next && (w + 2 * stride < p.work_items);
         TileRef nn = nxt;
+        int buf_nn = buf_next;
         if (has_next2) {
             nn = tile_ref(p, w + 2 * stride);
-            prepare(nn, buf);                  // tile k's bitmaps are no longer needed
+            // the other buffer is free: it held tile k's sub-grid (done) or nothing
+            buf_nn = nn.plane == nxt.plane ? buf_next : buf_next ^ 1;
+            prepare(nn, buf_nn);
         }
-        // Each thread owns the same tile slots for every tile, so it can swap
-        // tile k out of LDS and tile k+1 in, slot by slot, without a barrier.
+        // Each thread owns the same tile slots for every tile, so it swaps tile
+        // k out of LDS and tile k+1 in, slot by slot, without a barrier; the
+        // stores are issued only afterwards so that waiting for the loads of
+        // tile k+1 never waits for a store.
+        constexpr int kHalf = kPrefetch / 2;
+        {
+            char *origin = X + cur.base * p.row_bytes + cur.col0_bytes;
+            int32_t t_ = tid;
+            asm volatile("" : "+v"(t_));
+            int32_t lr = t_ / Wv, v = t_ - lr * Wv;
 #pragma unroll
-        for (int b = 0; b < kPrefetch; ++b) {
-            u32x4 *slot = reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(tid + b * kThreads) * 16);
-            const bool out_b = used_cur & (1u << b);
-            u32x4 val;
-            if (out_b) val = *slot;
-            if (has_next && (used_next & (1u << b))) *slot = pre[b];
-            if (out_b) {
-                const int32_t idx = tid + b * kThreads;
-                const int32_t lr = idx / Wv;
-                const int32_t v = idx - lr * Wv;
-                char *dst = X + global_row(p, cur.base, lr) * p.row_bytes + cur.col0_bytes + v * 16;
-                __builtin_nontemporal_store(val, reinterpret_cast<u32x4 *>(dst));
+            for (int h = 0; h < 2; ++h) {
+                u32x4 val[kHalf];
+#pragma unroll
+                for (int q = 0; q < kHalf; ++q) {
+                    const int b = h * kHalf + q;
+                    u32x4 *slot = reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(t_ + b * kThreads) * 16);
+                    if (used_cur & (1u << b)) val[q] = *slot;
+                    if (has_next && (used_next & (1u << b))) *slot = pre[b];
+                }
+#pragma unroll
+                for (int q = 0; q < kHalf; ++q) {
+                    const int b = h * kHalf + q;
+                    if (used_cur & (1u << b))
+                        __builtin_nontemporal_store(val[q], reinterpret_cast<u32x4 *>(origin + rowoff[lr] + v * 16));
+                    v += slot_dr;
+                    lr += slot_dq;
+                    if (v >= Wv) { v -= Wv; lr += 1; }
+                }
             }
         }
         if (!has_next) break;
         __syncthreads();
         uint32_t used_nn = 0;
-        if (has_next2) used_nn = fetch(nn, buf);
+        if (has_next2) used_nn = fetch(nn, buf_nn);
         w += stride;
         cur = nxt;
         used_cur = used_next;
+        buf_cur = buf_next;
         nxt = nn;
         used_next = used_nn;
+        buf_next = buf_nn;
         has_next = has_next2;
-        buf ^= 1;
     }
 }
 
@@ -348,7 +475,7 @@ int tree_size(int32_t M) { return M > 8 ? 16 : M > 4 ? 8 : M > 2 ? 4 : 2; }
 int64_t fixed_lds(int64_t rounds, int64_t rows, int64_t groups, int64_t F)
 {
     const int64_t rows_padded = (rows + 15) / 16 * 16;
-    return 2 * rounds * groups * 8 + 2 * rows_padded + F * groups * 4 + 64;
+    return 2 * rounds * groups * 8 + rows_padded * 8 + 2 * rows_padded + F * groups * 4 + 64;
 }
 
 }  // namespace
@@ -430,19 +557,41 @@ bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t r
 hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const uint8_t *masks, hipStream_t stream)
 {
     typedef void (*kernel_t)(char *, const uint8_t *, FusedPlan);
-    static const kernel_t table[2][4] = {
-        {fused_rounds_kernel<0, 2>, fused_rounds_kernel<0, 4>, fused_rounds_kernel<0, 8>, fused_rounds_kernel<0, 16>},
-        {fused_rounds_kernel<1, 2>, fused_rounds_kernel<1, 4>, fused_rounds_kernel<1, 8>, fused_rounds_kernel<1, 16>}};
-    static bool raised[2][4] = {{false, false, false, false}, {false, false, false, false}};
+    // shape index: 0 = (CV 1), 1 = (CV 2), 2 = (CV 4), 3 = (CV 4, 2 lanes per item), 4 = (CV 4, 4 lanes per item)
+#define MOSHPIT_ROW(DT, TR)                                                                              \
+    {fused_rounds_kernel<DT, TR, 1, 1>, fused_rounds_kernel<DT, TR, 2, 1>, fused_rounds_kernel<DT, TR, 4, 1>, \
+     nullptr, nullptr}
+#define MOSHPIT_ROW16(DT)                                                                                \
+    {fused_rounds_kernel<DT, 16, 1, 1>, fused_rounds_kernel<DT, 16, 2, 1>, fused_rounds_kernel<DT, 16, 4, 1>, \
+     fused_rounds_kernel<DT, 16, 4, 2>, fused_rounds_kernel<DT, 16, 4, 4>}
+    static const kernel_t table[2][4][5] = {
+        {MOSHPIT_ROW(0, 2), MOSHPIT_ROW(0, 4), MOSHPIT_ROW(0, 8), MOSHPIT_ROW16(0)},
+        {MOSHPIT_ROW(1, 2), MOSHPIT_ROW(1, 4), MOSHPIT_ROW(1, 8), MOSHPIT_ROW16(1)}};
+#undef MOSHPIT_ROW
+#undef MOSHPIT_ROW16
+    static bool raised[2][4][5] = {};
     static int compute_units = 0;
     const int tree = tree_size(plan.M);
     const int ti = tree == 2 ? 0 : tree == 4 ? 1 : tree == 8 ? 2 : 3;
-    const kernel_t kernel = table[dtype][ti];
-    if (!raised[dtype][ti]) {
+    // Every thread should have an item: prefer 4 columns per thread; if the tile
+    // is too narrow for that, let 2 or 4 lanes share a group's positions
+    // (8 < M <= 32), else narrow the per-thread column group.
+    const int64_t cols = plan.Wb / (dtype == 0 ? 4 : 2);
+    const int64_t items4 = plan.groups * (cols / 4);
+    int ci = 2;
+    if (items4 < kThreads) {
+        if (ti == 3 && plan.M <= 32) {
+            ci = items4 * 2 >= kThreads ? 3 : 4;
+        } else {
+            while (ci > 0 && plan.groups * (cols >> ci) < kThreads) --ci;
+        }
+    }
+    const kernel_t kernel = table[dtype][ti][ci];
+    if (!raised[dtype][ti][ci]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
-        raised[dtype][ti] = true;
+        raised[dtype][ti][ci] = true;
     }
     if (compute_units == 0) {
         int dev = 0;
