@@ -189,17 +189,10 @@ __device__ __forceinline__ void tree_block(const typename Cols<DT, CV>::elem_t *
 
 // TREE = size of the summation block actually needed: 16 for M > 8, else the
 // next power of two >= M (a 16-block padded with zeros gives the same bits).
-// Value of the lane whose index differs in bit 0 (CTRL 0xB1) or bit 1 (CTRL
-// 0x4E) within each group of four lanes (DPP quad_perm).
-template <int CTRL> __device__ __forceinline__ float quad_xor(float v)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
-
-// CV = columns one thread averages at a time; SPLIT = adjacent lanes that share
+// CV = columns one thread averages at a time; SPLIT = lanes of a wave that share
 // the positions of one group (chosen so that every thread has work even when
 // the tile is narrow).
-template <int DT, int TREE, int CV, int SPLIT>
+template <int DT, int TREE, int CV, int SPLIT, int PER>
 __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const uint8_t *__restrict__ masks, FusedPlan p)
 {
     typedef Cols<DT, CV> Q;
@@ -311,9 +304,12 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
         elem_t *T = reinterpret_cast<elem_t *>(tile);
         // SPLIT adjacent lanes share one (group, column chunk) item and take
         // SPLIT equal parts of its positions
+        // (sub is the slow lane index, so 8 consecutive lanes read 128 contiguous
+        // bytes of one row: no LDS bank conflicts)
         constexpr int kItemThreads = kThreads / SPLIT;
-        const int32_t sub = tid & (SPLIT - 1);
-        const int32_t it0 = tid / SPLIT;
+        constexpr int kLanesPerSub = 64 / SPLIT;
+        const int32_t sub = (tid & 63) / kLanesPerSub;
+        const int32_t it0 = (tid >> 6) * kLanesPerSub + (tid & (kLanesPerSub - 1));
         const int32_t g_first = it0 / cchunks, c_first = it0 - g_first * cchunks;
         const int32_t dg = kItemThreads / cchunks, dc = kItemThreads - dg * cchunks;
         for (int32_t r = 0; r < p.rounds; ++r) {
@@ -331,24 +327,24 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
                     elem_t *col = T + static_cast<int64_t>(lb[gl]) * W + cc * CV;
                     float acc[CV];
                     uint64_t mine = live;              // positions this thread writes back
+                    int32_t wj0 = 0;                   // first position of this thread's part
 #pragma unroll
                     for (int e = 0; e < CV; ++e) acc[e] = 0.f;
                     if constexpr (SPLIT > 1) {
-                        // M <= 32 here: one or two 16-position blocks, cut into SPLIT
-                        // balanced sub-trees of 4, 8 or 16 positions; the xor butterfly
-                        // over the SPLIT lanes adds them in the order of the full tree.
-                        const int32_t per = (p.M > 16 ? 32 : 16) / SPLIT;
-                        const int32_t j0 = sub * per;
-                        const uint32_t bits = static_cast<uint32_t>(live >> j0) & ((1u << per) - 1u);
+                        // M <= 32 here: SPLIT * PER = 16 or 32 positions (one or two
+                        // 16-position blocks) cut into SPLIT balanced sub-trees of PER
+                        // positions; the xor butterfly over the SPLIT lanes adds them in
+                        // the order of the full tree.
+                        const int32_t j0 = sub * PER;
+                        const uint32_t bits = static_cast<uint32_t>(live >> j0) & ((1u << PER) - 1u);
                         mine = static_cast<uint64_t>(bits) << j0;
+                        wj0 = j0;
                         float part[CV];
-                        if (per == 16) tree_block<DT, CV, 16, FLAT>(col, step, j0, p.M, bits, part);
-                        else if (per == 8) tree_block<DT, CV, 8, FLAT>(col, step, j0, p.M, bits, part);
-                        else tree_block<DT, CV, 4, FLAT>(col, step, j0, p.M, bits, part);
+                        tree_block<DT, CV, PER, FLAT>(col, step, j0, p.M, bits, part);
 #pragma unroll
                         for (int e = 0; e < CV; ++e) {
-                            part[e] += quad_xor<0xB1>(part[e]);                       // lane ^ 1
-                            if constexpr (SPLIT > 2) part[e] += quad_xor<0x4E>(part[e]);   // lane ^ 2
+                            part[e] += __shfl_xor(part[e], kLanesPerSub, 64);                          // sub ^ 1
+                            if constexpr (SPLIT > 2) part[e] += __shfl_xor(part[e], 2 * kLanesPerSub, 64);  // sub ^ 2
                             acc[e] += part[e];
                         }
                     } else if constexpr (TREE < 16) {
@@ -369,11 +365,20 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
                     const float k = static_cast<float>(cnt);
 #pragma unroll
                     for (int e = 0; e < CV; ++e) acc[e] = acc[e] / k;
-                    uint64_t rem = mine;
-                    while (rem != 0) {
-                        const int j = __builtin_ctzll(rem);
-                        rem &= rem - 1;
-                        Q::store(col + j * step, acc);
+                    if constexpr (SPLIT > 1 || TREE < 16) {
+                        // at most 16 positions, starting at wj0: straight-line predicated stores
+                        constexpr int kSpan = SPLIT > 1 ? PER : TREE;
+                        const uint32_t wbits = static_cast<uint32_t>(mine >> wj0);
+#pragma unroll
+                        for (int u = 0; u < kSpan; ++u)
+                            if ((wbits >> u) & 1u) Q::store(col + (wj0 + u) * step, acc);
+                    } else {
+                        uint64_t rem = mine;
+                        while (rem != 0) {
+                            const int j = __builtin_ctzll(rem);
+                            rem &= rem - 1;
+                            Q::store(col + j * step, acc);
+                        }
                     }
                 }
                 cc += dc;
@@ -557,19 +562,21 @@ bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t r
 hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const uint8_t *masks, hipStream_t stream)
 {
     typedef void (*kernel_t)(char *, const uint8_t *, FusedPlan);
-    // shape index: 0 = (CV 1), 1 = (CV 2), 2 = (CV 4), 3 = (CV 4, 2 lanes per item), 4 = (CV 4, 4 lanes per item)
-#define MOSHPIT_ROW(DT, TR)                                                                              \
-    {fused_rounds_kernel<DT, TR, 1, 1>, fused_rounds_kernel<DT, TR, 2, 1>, fused_rounds_kernel<DT, TR, 4, 1>, \
-     nullptr, nullptr}
-#define MOSHPIT_ROW16(DT)                                                                                \
-    {fused_rounds_kernel<DT, 16, 1, 1>, fused_rounds_kernel<DT, 16, 2, 1>, fused_rounds_kernel<DT, 16, 4, 1>, \
-     fused_rounds_kernel<DT, 16, 4, 2>, fused_rounds_kernel<DT, 16, 4, 4>}
-    static const kernel_t table[2][4][5] = {
+    // shape index: 0..2 = 1, 2, 4 columns per thread; 3..6 = 4 columns per thread with
+    // (lanes per item, positions per lane) = (2,8) (2,16) (4,4) (4,8)
+#define MOSHPIT_ROW(DT, TR)                                                                                       \
+    {fused_rounds_kernel<DT, TR, 1, 1, 0>, fused_rounds_kernel<DT, TR, 2, 1, 0>, fused_rounds_kernel<DT, TR, 4, 1, 0>, \
+     nullptr, nullptr, nullptr, nullptr}
+#define MOSHPIT_ROW16(DT)                                                                                         \
+    {fused_rounds_kernel<DT, 16, 1, 1, 0>, fused_rounds_kernel<DT, 16, 2, 1, 0>, fused_rounds_kernel<DT, 16, 4, 1, 0>, \
+     fused_rounds_kernel<DT, 16, 4, 2, 8>, fused_rounds_kernel<DT, 16, 4, 2, 16>,                                  \
+     fused_rounds_kernel<DT, 16, 4, 4, 4>, fused_rounds_kernel<DT, 16, 4, 4, 8>}
+    static const kernel_t table[2][4][7] = {
         {MOSHPIT_ROW(0, 2), MOSHPIT_ROW(0, 4), MOSHPIT_ROW(0, 8), MOSHPIT_ROW16(0)},
         {MOSHPIT_ROW(1, 2), MOSHPIT_ROW(1, 4), MOSHPIT_ROW(1, 8), MOSHPIT_ROW16(1)}};
 #undef MOSHPIT_ROW
 #undef MOSHPIT_ROW16
-    static bool raised[2][4][5] = {};
+    static bool raised[2][4][7] = {};
     static int compute_units = 0;
     const int tree = tree_size(plan.M);
     const int ti = tree == 2 ? 0 : tree == 4 ? 1 : tree == 8 ? 2 : 3;
@@ -581,7 +588,9 @@ hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const 
     int ci = 2;
     if (items4 < kThreads) {
         if (ti == 3 && plan.M <= 32) {
-            ci = items4 * 2 >= kThreads ? 3 : 4;
+            const bool two_blocks = plan.M > 16;
+            if (items4 * 2 >= kThreads) ci = two_blocks ? 4 : 3;
+            else ci = two_blocks ? 6 : 5;
         } else {
             while (ci > 0 && plan.groups * (cols >> ci) < kThreads) --ci;
         }
