@@ -69,6 +69,7 @@ def main() -> int:
     ap.add_argument("--cpu-cols", type=int, default=-1,
                     help="columns of the state the CPU oracle is timed on (0 = skip, -1 = auto)")
     ap.add_argument("--no-copy-probe", action="store_true")
+    ap.add_argument("--no-fused", action="store_true", help="skip the fused multi-round measurement")
     ap.add_argument("--tuning", type=str, default="", help="cols,unroll,nontemporal[,block,waves_per_cu] override for sweeps")
     ap.add_argument("--row-pad", type=int, default=0, help="extra elements between rows (row_stride = P + pad)")
     args = ap.parse_args()
@@ -150,6 +151,29 @@ def main() -> int:
         f"({100 * k1_gbps / HBM_PEAK_GBPS:.1f}% of peak), step {value:.0f} GB/s; dist/P after last step "
         f"{dists[-1] / w.P:.3e}")
 
+    # the same steps with fused multi-round passes (bit-identical results, fewer passes over HBM)
+    fused = None
+    if not args.no_fused:
+        fsteps = max(2, args.steps // 2)
+        for k in range(total_steps, total_steps + 1):
+            m.run(k * w.rounds, w.rounds, sched, flags=binding.RUN_FUSED)
+        m.sync()
+        f_masks = m.schedule_mask(sched, (total_steps + 1) * w.rounds, fsteps * w.rounds)
+        f_bytes = float((2.0 * s * w.P * live_in_groups(f_masks, w.M, w.d, (total_steps + 1) * w.rounds)).sum())
+        tf = time.perf_counter()
+        for k in range(total_steps + 1, total_steps + 1 + fsteps):
+            m.run(k * w.rounds, w.rounds, sched, flags=binding.RUN_FUSED)
+        m.sync()
+        f_elapsed = time.perf_counter() - tf
+        fused = {"ms_per_step": round(f_elapsed / fsteps * 1e3, 4),
+                 "rounds_per_s": round(w.rounds * fsteps / f_elapsed, 2),
+                 "effective_gbps": round(f_bytes / f_elapsed / 1e9, 1),
+                 "speedup_vs_single_rounds": round((float(round_ms.sum()) / args.steps) / (f_elapsed / fsteps * 1e3), 3),
+                 "note": "rounds only (no dist-to-mean); effective = single-round algorithmic bytes / time, "
+                         "may exceed the HBM peak because a fused pass touches HBM once for several rounds"}
+        log(f"[bench] fused passes: {fused['ms_per_step']} ms per {w.rounds} rounds, effective "
+            f"{fused['effective_gbps']} GB/s, {fused['speedup_vs_single_rounds']}x the single-round kernels")
+
     copy_gbps = None
     if not args.no_copy_probe:
         nbytes = min(w.N * w.P * s, 8 * 2 ** 30)
@@ -221,6 +245,7 @@ def main() -> int:
                      "frac": round(k1_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel": "group_mean_kernel", "bytes_per_launch": k1_bytes_per_launch,
                      "ms_per_launch": round(k1_ms_per_launch, 5)},
+        "fused": fused,
         "cpu_baseline": cpu,
     }
     m.close()

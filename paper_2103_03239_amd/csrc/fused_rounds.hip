@@ -548,6 +548,9 @@ bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t r
     wb = wb >= 128 ? wb / 128 * 128 : 0;
     if (wb < 128) return false;
     if (wb > valid) wb = valid;                  // a multiple of 16 (checked above)
+    // small states: narrower tiles so that every compute unit gets a few of them
+    const int64_t planes_total = N / rows;
+    while (wb >= 1024 && planes_total * ((valid + wb - 1) / wb) < 1024) wb = wb / 2 / 128 * 128;
     if (rows * (wb / 16) > static_cast<int64_t>(kThreads) * kPrefetch) return false;
     p.Wb = static_cast<int32_t>(wb);
     p.tile_bytes = static_cast<int32_t>(rows * wb);
