@@ -199,6 +199,35 @@ double oracle_dist_to_mean(const double *X, int64_t N, int64_t W, int64_t ld)
     return total / (double)N;
 }
 
+/*
+ * The same measure restricted to the peers that exist: when the grid is only
+ * partly filled (N < M^d, Sec. 3.1 after Eq. 2; the partly filled grids of
+ * Sec. 4.1 and Table 4) the mean and the average run over the rows with
+ * present[i] != 0 only.  present == NULL means every row.
+ */
+double oracle_dist_to_mean_subset(const double *X, int64_t N, int64_t W, int64_t ld, const uint8_t *present)
+{
+    int64_t n = 0;
+    for (int64_t i = 0; i < N; ++i)
+        if (present == NULL || present[i] != 0) ++n;
+    if (n == 0) return 0.0;
+    double total = 0.0;
+    for (int64_t c = 0; c < W; ++c) {
+        double s = 0.0;
+        for (int64_t i = 0; i < N; ++i)
+            if (present == NULL || present[i] != 0) s += X[i * ld + c];
+        double mu = s / (double)n;
+        double q = 0.0;
+        for (int64_t i = 0; i < N; ++i)
+            if (present == NULL || present[i] != 0) {
+                double e = X[i * ld + c] - mu;
+                q += e * e;
+            }
+        total += q;
+    }
+    return total / (double)n;
+}
+
 /* ---- seeded failure schedule ------------------------------------------ */
 
 /*

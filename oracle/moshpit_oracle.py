@@ -51,6 +51,8 @@ def _load():
         lib.oracle_quantize.argtypes = [_ptr, _i64, _i64, _i64, _i32]
         lib.oracle_dist_to_mean.argtypes = [_ptr, _i64, _i64, _i64]
         lib.oracle_dist_to_mean.restype = _f64
+        lib.oracle_dist_to_mean_subset.argtypes = [_ptr, _i64, _i64, _i64, _ptr]
+        lib.oracle_dist_to_mean_subset.restype = _f64
         lib.oracle_schedule_masks.argtypes = [_i32, _f64, _u64, _i32, _i64, _i64, _i32, _ptr]
         lib.oracle_run.argtypes = [_ptr, _i64, _i64, _i64, _i32, _i32, _i64, _i32, _ptr, _i32, _ptr]
         _lib = lib
@@ -113,6 +115,14 @@ def dist_to_mean(X: np.ndarray) -> float:
     X = _state(X)
     N, W = X.shape
     return float(_load().oracle_dist_to_mean(X.ctypes.data, N, W, X.strides[0] // 8))
+
+
+def dist_to_mean_subset(X: np.ndarray, present=None) -> float:
+    """Average distortion over the rows with present != 0 (None = all rows)."""
+    X = _state(X)
+    N, W = X.shape
+    keep, ptr = _mask_ptr(present, N)
+    return float(_load().oracle_dist_to_mean_subset(X.ctypes.data, N, W, X.strides[0] // 8, ptr))
 
 
 def schedule_masks(kind: int, p: float, seed: int, down: int, N: int, t0: int, rounds: int) -> np.ndarray:

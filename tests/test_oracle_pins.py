@@ -263,30 +263,60 @@ def test_expected_distortion_closed_form():
 
 
 # --------------------------------------------------------------------------
-# Table 4 of the paper, N = 1024 (M = 32, d = 2)
+# Table 4 of the paper: all sixteen Moshpit entries (32x32 grid)
 # --------------------------------------------------------------------------
 
-def rounds_to_error(p, seed, thresholds, max_rounds=30):
+def rounds_to_error(n, p, seed, thresholds=(1e-9, 1e-4), max_rounds=50):
+    """One restart of the paper's averaging experiment (Sec. 4.1): n peers sit
+    on a uniformly random subset of the 32x32 grid's vertices (the other
+    vertices stay empty for the whole run), hold scalar N(0,1) values, fail
+    independently per round with probability p and return in the next round;
+    the error is the average squared difference to the mean over the n peers."""
     rng = np.random.default_rng(seed)
+    present = np.zeros(1024, dtype=np.uint8)
+    present[rng.choice(1024, size=n, replace=False)] = 1
     X = rng.normal(size=(1024, 1))
     masks = orc.schedule_masks(1, p, seed, 0, 1024, 0, max_rounds)
-    dist = orc.run(X, 32, 2, 0, max_rounds, masks, want_dist=True)
-    return [int(np.argmax(dist <= th)) if (dist <= th).any() else max_rounds for th in thresholds]
+    hit = [None] * len(thresholds)
+    for t in range(max_rounds + 1):
+        dist = orc.dist_to_mean_subset(X, present)
+        for k, th in enumerate(thresholds):
+            if hit[k] is None and dist <= th:
+                hit[k] = t
+        if all(h is not None for h in hit) or t == max_rounds:
+            break
+        orc.round_(X, 32, 2, t, present & masks[t])
+    return [h if h is not None else max_rounds for h in hit]
 
 
 def test_table4_moshpit_column(golden_dir):
-    """p = 0 must give exactly 2.0 (2.0).  With failures the paper's simulator
-    is not specified in every detail (what a failed peer holds when it comes
-    back), so those rows are only required to land within half a round."""
-    rows = np.loadtxt(os.path.join(golden_dir, "table4_moshpit_n1024.txt"), comments="#")
-    for p, want9, want4 in rows:
-        got = np.array([rounds_to_error(p, 1000 + s, (1e-9, 1e-4)) for s in range(100)], dtype=float)
+    """The oracle's semantics (static grid, axes cycling, survivors average, a
+    failed peer keeps its stale value and stays in the metric, empty vertices
+    never take part) reproduce every Moshpit entry of Table 4.  N = 1024,
+    p = 0 is exact; the others are means over 100 restarts and must land within
+    0.4 round of the printed value (the paper prints one decimal; the standard
+    error of such a mean is about 0.1)."""
+    rows = np.loadtxt(os.path.join(golden_dir, "table4_moshpit.txt"), comments="#")
+    assert len(rows) == 16
+    for n, p, want9, want4 in rows:
+        got = np.array([rounds_to_error(int(n), p, 7000 + s) for s in range(100)], dtype=float)
         m9, m4 = got[:, 0].mean(), got[:, 1].mean()
-        if p == 0:
+        if n == 1024 and p == 0:
             assert (m9, m4) == (2.0, 2.0)
         else:
-            assert abs(m9 - want9) <= 0.5, (p, m9, want9)
-            assert abs(m4 - want4) <= 0.5, (p, m4, want4)
+            assert abs(m9 - want9) <= 0.4, (n, p, m9, want9)
+            assert abs(m4 - want4) <= 0.4, (n, p, m4, want4)
+
+
+def test_dist_subset_is_numpy_definition():
+    rng = np.random.default_rng(12)
+    X = rng.normal(size=(30, 5)) + 2
+    present = (rng.random(30) < 0.6).astype(np.uint8)
+    sub = X[present == 1]
+    want = ((sub - sub.mean(axis=0)) ** 2).sum() / len(sub)
+    assert abs(orc.dist_to_mean_subset(X, present) - want) <= 1e-13 * want
+    assert orc.dist_to_mean_subset(X, None) == orc.dist_to_mean(X)
+    assert orc.dist_to_mean_subset(X, np.zeros(30, np.uint8)) == 0.0
 
 
 # --------------------------------------------------------------------------
