@@ -136,6 +136,14 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
  * GPU.  out_host: host, one double. */
 int moshpit_dist_to_mean(moshpit_ctx *h, double *out_host);
 
+/* The same measure over the peers that exist when the grid is only partly
+ * filled (Sec. 3.1 after Eq. 2; the partly filled grids of Sec. 4.1 / Table 4):
+ * mean and average run over the rows with present_host[i] != 0 only.  A vertex
+ * without a peer is modelled as a row that never takes part in a round (its
+ * alive byte is 0 in every round) and is left out here.  present_host: host,
+ * N bytes, NULL = every row.  Waits for the GPU.  All rows absent gives 0. */
+int moshpit_dist_to_mean_subset(moshpit_ctx *h, const uint8_t *present_host, double *out_host);
+
 /* Group key of every peer for round t (Eq. 1 on the static grid: the d-1
  * coordinates other than t mod d, read in increasing coordinate order as a
  * base-M number).  Computed on the device; waits.  keys_host: host, N int32. */

@@ -22,7 +22,7 @@ RUN_DEFAULT, RUN_FUSED = 0, 1
 
 EXPORTS = [
     "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",
-    "moshpit_run", "moshpit_dist_to_mean", "moshpit_group_keys", "moshpit_schedule_mask",
+    "moshpit_run", "moshpit_dist_to_mean", "moshpit_dist_to_mean_subset", "moshpit_group_keys", "moshpit_schedule_mask",
     "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
 ]
 
@@ -64,6 +64,7 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_round_dev.argtypes = [vp, i64, vp]
     lib.moshpit_run.argtypes = [vp, i64, i32, ctypes.POINTER(_CSchedule), i32, vp, vp]
     lib.moshpit_dist_to_mean.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+    lib.moshpit_dist_to_mean_subset.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.moshpit_group_keys.argtypes = [vp, i64, vp]
     lib.moshpit_schedule_mask.argtypes = [vp, ctypes.POINTER(_CSchedule), i64, i32, vp]
     lib.moshpit_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32]
@@ -177,6 +178,18 @@ class Moshpit:
     def dist_to_mean(self) -> float:
         out = ctypes.c_double()
         self._check(self._lib.moshpit_dist_to_mean(self._h, ctypes.byref(out)), "dist_to_mean")
+        return out.value
+
+    def dist_to_mean_subset(self, present) -> float:
+        """present: uint8 [N], non-zero = the row holds a peer (None = all rows)."""
+        out = ctypes.c_double()
+        ptr = None
+        if present is not None:
+            keep = np.ascontiguousarray(present, dtype=np.uint8)
+            if keep.shape != (self.N,):
+                raise ValueError("present mask must have shape (N,)")
+            ptr = keep.ctypes.data
+        self._check(self._lib.moshpit_dist_to_mean_subset(self._h, ptr, ctypes.byref(out)), "dist_to_mean_subset")
         return out.value
 
     def group_keys(self, t: int) -> np.ndarray:

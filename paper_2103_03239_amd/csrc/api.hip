@@ -22,6 +22,7 @@ struct moshpit_ctx {
     hipStream_t stream = nullptr;
 
     uint8_t *d_round_mask = nullptr;   // N bytes, for moshpit_round(host mask)
+    uint8_t *d_present = nullptr;      // N bytes, for moshpit_dist_to_mean_subset
     uint8_t *d_masks = nullptr;        // mask_rounds_cap * N bytes, for runs
     int64_t mask_rounds_cap = 0;
     int32_t *d_keys = nullptr;         // N
@@ -152,7 +153,8 @@ int queue_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev)
 
 int queue_dist(moshpit_ctx *h, double *out_dev)
 {
-    HIP_TRY(h, launch_dist_to_mean(h->X, h->dtype, h->N, h->P, h->row_stride, h->d_partials, out_dev, h->stream));
+    HIP_TRY(h, launch_dist_to_mean(h->X, h->dtype, h->N, h->P, h->row_stride, h->d_partials, out_dev, nullptr, 0,
+                                   h->N, h->stream));
     return MOSHPIT_OK;
 }
 
@@ -199,6 +201,7 @@ int moshpit_destroy(moshpit_ctx *h)
     (void)hipStreamSynchronize(h->stream);
     for (hipEvent_t ev : h->events) (void)hipEventDestroy(ev);
     if (h->d_round_mask) (void)hipFree(h->d_round_mask);
+    if (h->d_present) (void)hipFree(h->d_present);
     if (h->d_masks) (void)hipFree(h->d_masks);
     if (h->d_keys) (void)hipFree(h->d_keys);
     if (h->d_partials) (void)hipFree(h->d_partials);
@@ -341,6 +344,31 @@ int moshpit_dist_to_mean(moshpit_ctx *h, double *out_host)
     if (!out_host) return fail(h, MOSHPIT_EINVAL, "out is NULL");
     rc = queue_dist(h, h->d_dist);
     if (rc != MOSHPIT_OK) return rc;
+    HIP_TRY(h, hipMemcpyAsync(out_host, h->d_dist, sizeof(double), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return MOSHPIT_OK;
+}
+
+int moshpit_dist_to_mean_subset(moshpit_ctx *h, const uint8_t *present_host, double *out_host)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (!out_host) return fail(h, MOSHPIT_EINVAL, "out is NULL");
+    if (!present_host) return moshpit_dist_to_mean(h, out_host);
+    int64_t first = -1, n = 0;
+    for (int64_t i = 0; i < h->N; ++i)
+        if (present_host[i] != 0) {
+            if (first < 0) first = i;
+            ++n;
+        }
+    if (n == 0) {
+        *out_host = 0.0;
+        return MOSHPIT_OK;
+    }
+    if (!h->d_present) HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_present), static_cast<size_t>(h->N)));
+    HIP_TRY(h, hipMemcpyAsync(h->d_present, present_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, launch_dist_to_mean(h->X, h->dtype, h->N, h->P, h->row_stride, h->d_partials, h->d_dist, h->d_present,
+                                   first, n, h->stream));
     HIP_TRY(h, hipMemcpyAsync(out_host, h->d_dist, sizeof(double), hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return MOSHPIT_OK;

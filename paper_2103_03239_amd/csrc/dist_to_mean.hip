@@ -6,7 +6,8 @@
 // in binary64, s1 = sum_i (x_ic - x_0c) and s2 = sum_i (x_ic - x_0c)^2 and uses
 // sum_i (x_ic - mean_c)^2 = s2 - s1^2 / N.  Shifting by row 0 keeps the
 // subtraction harmless once the peers have (nearly) agreed: all differences
-// are then tiny and exact in binary64.
+// are then tiny and exact in binary64.  With a `present` mask (a partly filled
+// grid) the same runs over the rows that hold a peer, shifted by the first one.
 //
 // Mapping.  A block owns a tile of 64 vectors (one 128-bit vector per lane,
 // 1 KiB per row); its W waves take rows w, w+W, ... with 8 row loads in flight
@@ -63,11 +64,16 @@ template <> struct Wide<1, 1> {
 
 // X         byte pointer to element (row 0, first column of this launch)
 // nvec      vectors of VE elements per row covered by this launch
-// partials  one double per block: sum over the block's columns of s2 - s1^2/N
+// partials  one double per block: sum over the block's columns of s2 - s1^2/n
+// present   nullptr, or N bytes: rows with 0 are left out of mean and sum
+//           (vertices of a partly filled grid that hold no peer)
+// first     index of the first row that counts; n = number of rows that count
 template <int DT, int VE>
 __global__ __launch_bounds__(kWaves * 64) void dist_partial_kernel(const char *__restrict__ X, int64_t row_bytes,
                                                                     int64_t nvec, int64_t N,
-                                                                    double *__restrict__ partials)
+                                                                    double *__restrict__ partials,
+                                                                    const uint8_t *__restrict__ present,
+                                                                    int64_t first, int64_t n)
 {
     typedef Wide<DT, VE> V;
     typedef typename V::mem_t mem_t;
@@ -83,7 +89,7 @@ __global__ __launch_bounds__(kWaves * 64) void dist_partial_kernel(const char *_
     double x0[NE], s1[NE], s2[NE];
 #pragma unroll
     for (int e = 0; e < NE; ++e) { x0[e] = 0.0; s1[e] = 0.0; s2[e] = 0.0; }
-    if (valid) V::widen(*reinterpret_cast<const mem_t *>(col), x0);
+    if (valid) V::widen(*reinterpret_cast<const mem_t *>(col + first * row_bytes), x0);
 
     for (int64_t i0 = wave; i0 < N; i0 += kWaves * kRowsInFlight) {
         mem_t buf[kRowsInFlight];
@@ -91,7 +97,7 @@ __global__ __launch_bounds__(kWaves * 64) void dist_partial_kernel(const char *_
 #pragma unroll
         for (int u = 0; u < kRowsInFlight; ++u) {
             const int64_t i = i0 + static_cast<int64_t>(u) * kWaves;
-            have[u] = valid && i < N;
+            have[u] = valid && i < N && (present == nullptr || present[i] != 0);
             if (have[u]) buf[u] = *reinterpret_cast<const mem_t *>(col + i * row_bytes);
         }
 #pragma unroll
@@ -120,7 +126,7 @@ __global__ __launch_bounds__(kWaves * 64) void dist_partial_kernel(const char *_
             double t1 = 0.0, t2 = 0.0;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) { t1 += sh[0][w][lane]; t2 += sh[1][w][lane]; }
-            if (valid) colsum += t2 - t1 * t1 / static_cast<double>(N);
+            if (valid) colsum += t2 - t1 * t1 / static_cast<double>(n);
         }
         __syncthreads();
     }
@@ -132,7 +138,7 @@ __global__ __launch_bounds__(kWaves * 64) void dist_partial_kernel(const char *_
 }
 
 __global__ __launch_bounds__(256) void dist_final_kernel(const double *__restrict__ partials, int64_t count,
-                                                         int64_t N, double *__restrict__ out)
+                                                         int64_t n, double *__restrict__ out)
 {
     __shared__ double sh[256];
     double acc = 0.0;
@@ -143,7 +149,7 @@ __global__ __launch_bounds__(256) void dist_final_kernel(const double *__restric
         if (static_cast<int>(threadIdx.x) < s) sh[threadIdx.x] += sh[threadIdx.x + s];
         __syncthreads();
     }
-    if (threadIdx.x == 0) out[0] = sh[0] / static_cast<double>(N);
+    if (threadIdx.x == 0) out[0] = sh[0] / static_cast<double>(n);
 }
 
 struct Split {
@@ -174,7 +180,8 @@ int64_t dist_partials_count(int dtype, int64_t P, int64_t row_stride, const void
 }
 
 hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, int64_t row_stride,
-                               double *partials, double *out, hipStream_t stream)
+                               double *partials, double *out, const uint8_t *present, int64_t first, int64_t n,
+                               hipStream_t stream)
 {
     const Split s = split_row(dtype, P, row_stride, X);
     if (s.blocks_vec > 0x7fffffffLL || s.blocks_tail > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -185,9 +192,9 @@ hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, i
     if (s.blocks_vec > 0) {
         const dim3 grid(static_cast<uint32_t>(s.blocks_vec));
         if (dtype == 0)
-            dist_partial_kernel<0, 4><<<grid, block, 0, stream>>>(base, row_bytes, s.nvec, N, partials);
+            dist_partial_kernel<0, 4><<<grid, block, 0, stream>>>(base, row_bytes, s.nvec, N, partials, present, first, n);
         else
-            dist_partial_kernel<1, 8><<<grid, block, 0, stream>>>(base, row_bytes, s.nvec, N, partials);
+            dist_partial_kernel<1, 8><<<grid, block, 0, stream>>>(base, row_bytes, s.nvec, N, partials, present, first, n);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -196,13 +203,13 @@ hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, i
         const char *tbase = base + s.tail0 * esize;
         double *tpart = partials + s.blocks_vec;
         if (dtype == 0)
-            dist_partial_kernel<0, 1><<<grid, block, 0, stream>>>(tbase, row_bytes, P - s.tail0, N, tpart);
+            dist_partial_kernel<0, 1><<<grid, block, 0, stream>>>(tbase, row_bytes, P - s.tail0, N, tpart, present, first, n);
         else
-            dist_partial_kernel<1, 1><<<grid, block, 0, stream>>>(tbase, row_bytes, P - s.tail0, N, tpart);
+            dist_partial_kernel<1, 1><<<grid, block, 0, stream>>>(tbase, row_bytes, P - s.tail0, N, tpart, present, first, n);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    dist_final_kernel<<<dim3(1), dim3(256), 0, stream>>>(partials, s.blocks_vec + s.blocks_tail, N, out);
+    dist_final_kernel<<<dim3(1), dim3(256), 0, stream>>>(partials, s.blocks_vec + s.blocks_tail, n, out);
     return hipGetLastError();
 }
 

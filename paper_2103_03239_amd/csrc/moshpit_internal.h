@@ -38,9 +38,11 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
 int64_t dist_partials_count(int dtype, int64_t P, int64_t row_stride, const void *X);
 
 // Queue the distortion reduction: partials (device, dist_partials_count
-// doubles) then out[0] = (sum of partials) / N.
+// doubles) then out[0] = (sum of partials) / n.  present: device, N bytes, or
+// nullptr (every row counts); first = first row that counts, n = how many do.
 hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, int64_t row_stride,
-                               double *partials, double *out, hipStream_t stream);
+                               double *partials, double *out, const uint8_t *present, int64_t first, int64_t n,
+                               hipStream_t stream);
 
 // Queue the failure-schedule generator: masks[r][i] (device, rounds*N bytes).
 hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down, int64_t N, int64_t t0,

@@ -319,3 +319,40 @@ def test_fused_full_size_matches_single_rounds(cfg):
     say(f"  single rounds {ms_a.sum():.3f} ms, fused {ms_b.sum():.3f} ms")
     assert torch.equal(B.index_select(1, cols), a_cols)
     assert torch.equal(B.sum(dim=0, dtype=torch.float64), a_sum)
+
+
+# --------------------------------------------------------------------------
+# partly filled grids (N peers on a subset of the M^d vertices)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,d,n_present,dtype,P,p", [(32, 2, 512, 0, 1_000, 0.01), (32, 2, 900, 0, 333, 0.0),
+                                                      (8, 3, 300, 1, 2_048, 0.05), (4, 2, 1, 0, 64, 0.0)])
+def test_partly_filled_grid(M, d, n_present, dtype, P, p):
+    """Empty vertices never take part and are left out of the error measure
+    (the setting of Table 4's N < 1024 rows)."""
+    N, rounds = M ** d, 7
+    rng = np.random.default_rng(N + n_present)
+    present = np.zeros(N, dtype=np.uint8)
+    present[rng.choice(N, size=n_present, replace=False)] = 1
+    w = inputs.Workload("partial", N, M, d, P, dtype, "normal", 1, p, 0, rounds, 77, 78)
+    say(f"partial grid {w} present={n_present}")
+    X = inputs.make_state(w, DEV)
+    ref = to_f64(X).copy()
+    masks = orc.schedule_masks(1, p, 78, 0, N, 0, rounds) & present
+    floor = dist_floor(P, dtype, 1.0)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(X)
+        for t in range(rounds):
+            got = m.dist_to_mean_subset(present)
+            want = orc.dist_to_mean_subset(ref, present)
+            assert abs(got - want) <= TOL[dtype] * want + floor, (t, got, want)
+            m.round(t, masks[t])
+            orc.round_(ref, M, d, t, masks[t])
+        m.sync()
+        assert_state_close(to_f64(X), ref, TOL[dtype], "partial grid")
+        assert m.dist_to_mean_subset(None) == m.dist_to_mean()
+        assert m.dist_to_mean_subset(np.zeros(N, np.uint8)) == 0.0
+    # rows of empty vertices were never written
+    X0 = inputs.make_state(w, DEV)
+    empty = torch.from_numpy(present == 0).to(DEV)
+    assert torch.equal(X[empty], X0[empty])
