@@ -286,6 +286,87 @@ int oracle_schedule_masks(int32_t kind, double p, uint64_t seed, int32_t down,
     return 0;
 }
 
+/* ---- averaging in random groups ---------------------------------------- */
+
+/*
+ * The simplified scheme analysed in Thm 3.2 (and compared in Sec. 4.1): in
+ * every iteration the peers are permuted at random and the permutation is cut
+ * into consecutive groups; every group averages (proof of Thm 3.2, App. C.3:
+ * "we generate a random permutation and take contiguous subgroups").
+ *
+ * The permutation of round t orders the peers by the 64-bit key
+ *   key(seed,t,i) = mix( mix(seed + 0xD1B54A32D192ED03*(t+1)) ^ i ),
+ * ties broken by peer index (same mixer as the failure schedule, another
+ * stream constant).  perm[r] = peer of rank r.  Ranks by plain counting.
+ */
+static uint64_t order_key(uint64_t seed, int64_t t, int64_t i)
+{
+    return mix64(mix64(seed + 0xD1B54A32D192ED03ull * (uint64_t)(t + 1)) ^ (uint64_t)i);
+}
+
+int oracle_random_permutation(uint64_t seed, int64_t t, int64_t N, int64_t *perm)
+{
+    if (t < 0 || N < 0) return -1;
+    for (int64_t i = 0; i < N; ++i) {
+        uint64_t ki = order_key(seed, t, i);
+        int64_t rank = 0;
+        for (int64_t j = 0; j < N; ++j) {
+            uint64_t kj = order_key(seed, t, j);
+            if (kj < ki || (kj == ki && j < i)) ++rank;
+        }
+        perm[rank] = i;
+    }
+    return 0;
+}
+
+/*
+ * One round over explicit groups: group g consists of the peers
+ * index[g*group_size .. min(n_index, (g+1)*group_size) - 1]; its members that
+ * take part (alive != 0; alive == NULL means all) are replaced by their mean.
+ * `index` must not list a peer twice.
+ */
+int oracle_grouped_round(double *X, int64_t N, int64_t W, int64_t ld, const int64_t *index, int64_t n_index,
+                         int32_t group_size, const uint8_t *alive)
+{
+    if (group_size < 1 || n_index < 0) return -1;
+    for (int64_t q = 0; q < n_index; ++q)
+        if (index[q] < 0 || index[q] >= N) return -1;
+    double *mean = (double *)malloc(sizeof(double) * (size_t)(W > 0 ? W : 1));
+    if (!mean) return -2;
+    for (int64_t g0 = 0; g0 < n_index; g0 += group_size) {
+        int64_t g1 = g0 + group_size < n_index ? g0 + group_size : n_index;
+        int64_t k = 0;
+        for (int64_t c = 0; c < W; ++c) mean[c] = 0.0;
+        for (int64_t q = g0; q < g1; ++q) {
+            if (alive != NULL && alive[index[q]] == 0) continue;
+            const double *row = X + index[q] * ld;
+            for (int64_t c = 0; c < W; ++c) mean[c] += row[c];
+            ++k;
+        }
+        if (k == 0) continue;
+        for (int64_t c = 0; c < W; ++c) mean[c] = mean[c] / (double)k;
+        for (int64_t q = g0; q < g1; ++q) {
+            if (alive != NULL && alive[index[q]] == 0) continue;
+            double *row = X + index[q] * ld;
+            for (int64_t c = 0; c < W; ++c) row[c] = mean[c];
+        }
+    }
+    free(mean);
+    return 0;
+}
+
+/* Round t of random-group averaging with groups of `group_size` peers. */
+int oracle_random_groups_round(double *X, int64_t N, int64_t W, int64_t ld, uint64_t seed, int64_t t,
+                               int32_t group_size, const uint8_t *alive)
+{
+    int64_t *perm = (int64_t *)malloc(sizeof(int64_t) * (size_t)(N > 0 ? N : 1));
+    if (!perm) return -2;
+    int rc = oracle_random_permutation(seed, t, N, perm);
+    if (rc == 0) rc = oracle_grouped_round(X, N, W, ld, perm, N, group_size, alive);
+    free(perm);
+    return rc;
+}
+
 /* ---- several rounds ---------------------------------------------------- */
 
 /*

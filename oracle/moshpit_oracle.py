@@ -54,6 +54,9 @@ def _load():
         lib.oracle_dist_to_mean_subset.argtypes = [_ptr, _i64, _i64, _i64, _ptr]
         lib.oracle_dist_to_mean_subset.restype = _f64
         lib.oracle_schedule_masks.argtypes = [_i32, _f64, _u64, _i32, _i64, _i64, _i32, _ptr]
+        lib.oracle_random_permutation.argtypes = [_u64, _i64, _i64, _ptr]
+        lib.oracle_grouped_round.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _i64, _i32, _ptr]
+        lib.oracle_random_groups_round.argtypes = [_ptr, _i64, _i64, _i64, _u64, _i64, _i32, _ptr]
         lib.oracle_run.argtypes = [_ptr, _i64, _i64, _i64, _i32, _i32, _i64, _i32, _ptr, _i32, _ptr]
         _lib = lib
     return _lib
@@ -131,6 +134,30 @@ def schedule_masks(kind: int, p: float, seed: int, down: int, N: int, t0: int, r
     _check(_load().oracle_schedule_masks(kind, float(p), seed, down, N, t0, rounds,
                                          masks.ctypes.data), "schedule_masks")
     return masks
+
+
+def random_permutation(seed: int, t: int, N: int) -> np.ndarray:
+    perm = np.empty(N, dtype=np.int64)
+    _check(_load().oracle_random_permutation(seed, t, N, perm.ctypes.data), "random_permutation")
+    return perm
+
+
+def grouped_round(X: np.ndarray, index, group_size: int, alive=None) -> None:
+    """Average consecutive chunks of `group_size` entries of the peer list `index`."""
+    X = _state(X)
+    N, W = X.shape
+    idx = np.ascontiguousarray(index, dtype=np.int64)
+    keep, ptr = _mask_ptr(alive, N)
+    _check(_load().oracle_grouped_round(X.ctypes.data, N, W, X.strides[0] // 8, idx.ctypes.data, len(idx),
+                                        group_size, ptr), "grouped_round")
+
+
+def random_groups_round(X: np.ndarray, seed: int, t: int, group_size: int, alive=None) -> None:
+    X = _state(X)
+    N, W = X.shape
+    keep, ptr = _mask_ptr(alive, N)
+    _check(_load().oracle_random_groups_round(X.ctypes.data, N, W, X.strides[0] // 8, seed, t, group_size, ptr),
+           "random_groups_round")
 
 
 def run(X: np.ndarray, M: int, d: int, t0: int, rounds: int, masks=None,

@@ -320,6 +320,76 @@ def test_dist_subset_is_numpy_definition():
 
 
 # --------------------------------------------------------------------------
+# averaging in random groups: the exact contraction rate of Thm 3.2
+# --------------------------------------------------------------------------
+
+def test_random_groups_exact_rate_by_enumeration():
+    """Thm 3.2 states E[dist after one iteration] = ((r-1)/N + r/N^2) * dist
+    before, for a uniformly random permutation cut into r groups.  Its proof
+    takes the probability that two given peers share group i as M_i(M_i-1)/N^2;
+    for a permutation it is M_i(M_i-1)/(N(N-1)), which turns the rate into
+    (r-1)/(N-1) exactly.  The two agree to O(1/N^2) (0.030304 vs 0.030303 for
+    N = 1024, r = 32).  Enumerating all N! permutations for tiny N and feeding
+    each to the oracle's grouped round must give the exact rate."""
+    for N, gs, r in ((4, 2, 2), (5, 2, 3), (6, 3, 2), (6, 2, 3)):
+        rng = np.random.default_rng(N)
+        X0 = rng.normal(size=(N, 2)) + 1.0
+        d0 = orc.dist_to_mean(X0)
+        acc, cnt = 0.0, 0
+        for perm in itertools.permutations(range(N)):
+            X = X0.copy()
+            orc.grouped_round(X, perm, gs)
+            acc += orc.dist_to_mean(X)
+            cnt += 1
+            assert np.allclose(X.sum(axis=0), X0.sum(axis=0), atol=1e-13, rtol=0)
+        exact = (r - 1) / (N - 1)
+        printed = (r - 1) / N + r / N ** 2
+        assert abs(acc / cnt - exact * d0) <= 1e-12 * d0, (N, acc / cnt / d0, exact)
+        assert abs(printed - exact) <= 1.0 / N ** 2 + 1e-15       # the printed rate is the same to O(1/N^2)
+
+
+def test_random_groups_seeded_rate():
+    """The seeded permutation behaves like a uniform one: the mean contraction
+    over 1000 seeds matches the rate of Thm 3.2 for N = 64, r = 8 (printed
+    0.11133, exact 0.11111) within 2 %; over T rounds the rate compounds."""
+    N, gs, r = 64, 8, 8
+    rng = np.random.default_rng(64)
+    X0 = rng.normal(size=(N, 4))
+    d0 = orc.dist_to_mean(X0)
+    rate = (r - 1) / (N - 1)
+    one, three = [], []
+    for seed in range(1000):
+        X = X0.copy()
+        for t in range(3):
+            orc.random_groups_round(X, seed, t, gs)
+            if t == 0:
+                one.append(orc.dist_to_mean(X) / d0)
+        three.append(orc.dist_to_mean(X) / d0)
+    assert abs(np.mean(one) - rate) <= 0.02 * rate
+    assert abs(np.mean(three) - rate ** 3) <= 0.08 * rate ** 3
+
+
+def test_random_permutation_is_a_permutation_and_matches_python():
+    N = 300
+    perm = orc.random_permutation(11, 5, N)
+    assert sorted(perm.tolist()) == list(range(N))
+    keys = [py_mix(py_mix((11 + 0xD1B54A32D192ED03 * 6) & MASK64) ^ i) for i in range(N)]
+    assert perm.tolist() == sorted(range(N), key=lambda i: (keys[i], i))
+    assert not np.array_equal(perm, orc.random_permutation(11, 6, N))
+    # a grouped round with failures: the absent peers keep their rows, the others average
+    rng = np.random.default_rng(3)
+    X0 = rng.normal(size=(N, 3))
+    alive = (rng.random(N) > 0.2).astype(np.uint8)
+    X = X0.copy()
+    orc.random_groups_round(X, 11, 5, 7, alive)
+    assert np.array_equal(X[alive == 0], X0[alive == 0])
+    for g0 in range(0, N, 7):
+        members = [i for i in perm[g0:g0 + 7] if alive[i]]
+        if members:
+            assert np.allclose(X[members], X0[members].mean(axis=0), atol=1e-15, rtol=0)
+
+
+# --------------------------------------------------------------------------
 # variance bound with peers absent for the whole run (App. C.4)
 # --------------------------------------------------------------------------
 
