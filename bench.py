@@ -174,6 +174,27 @@ def main() -> int:
         log(f"[bench] fused passes: {fused['ms_per_step']} ms per {w.rounds} rounds, effective "
             f"{fused['effective_gbps']} GB/s, {fused['speedup_vs_single_rounds']}x the single-round kernels")
 
+    # averaging in random groups of M peers (the simplified scheme of Thm 3.2): same kernel, rows
+    # addressed through a seeded permutation; every peer takes part, so a round moves 2*s*N*P bytes
+    random_groups = None
+    if not args.no_fused and w.N <= 65536:
+        stream = torch.cuda.current_stream(dev)
+        for t in range(2):
+            m.random_groups_round(t, 77, w.M)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        m.sync()
+        reps = 8
+        e0.record(stream)
+        for t in range(2, 2 + reps):
+            m.random_groups_round(t, 77, w.M)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        rg_ms = e0.elapsed_time(e1) / reps
+        random_groups = {"group_size": w.M, "ms_per_round": round(rg_ms, 4),
+                         "gbps": round(2.0 * s * w.N * w.P / (rg_ms * 1e-3) / 1e9, 1),
+                         "note": "includes the permutation kernel of every round"}
+        log(f"[bench] random groups of {w.M}: {rg_ms:.3f} ms per round, {random_groups['gbps']} GB/s")
+
     copy_gbps = None
     if not args.no_copy_probe:
         nbytes = min(w.N * w.P * s, 8 * 2 ** 30)
@@ -246,6 +267,7 @@ def main() -> int:
                      "kernel": "group_mean_kernel", "bytes_per_launch": k1_bytes_per_launch,
                      "ms_per_launch": round(k1_ms_per_launch, 5)},
         "fused": fused,
+        "random_groups": random_groups,
         "cpu_baseline": cpu,
     }
     m.close()

@@ -155,6 +155,28 @@ int moshpit_group_keys(moshpit_ctx *h, int64_t t, int32_t *keys_host);
 int moshpit_schedule_mask(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t rounds,
                           uint8_t *masks_host);
 
+/* Averaging in random groups: the simplified scheme analysed in Thm 3.2 and
+ * compared in Sec. 4.1.  Round t orders the peers by the key
+ *   mix(mix(seed + 0xD1B54A32D192ED03*(t+1)) ^ i)       (mix as for the schedule)
+ * with ties broken by peer index, cuts the resulting permutation into
+ * consecutive groups of group_size peers (the last one may be shorter) and
+ * replaces the members of every group that take part by their mean (App. C.3,
+ * proof of Thm 3.2).  1 <= group_size <= 64, N <= 65536.  alive_host as in
+ * moshpit_round.  Queued on the bound stream.
+ * moshpit_random_permutation returns the permutation of round t (host, N
+ * int32, perm[r] = peer of rank r), computed by the same device kernel; waits. */
+int moshpit_random_groups_round(moshpit_ctx *h, int64_t t, uint64_t seed, int32_t group_size,
+                                const uint8_t *alive_host);
+int moshpit_random_permutation(moshpit_ctx *h, int64_t t, uint64_t seed, int32_t *perm_host);
+
+/* One round over caller-defined groups: consecutive chunks of group_size entries
+ * of the peer list index_host[0..n_index) (host; distinct peers in [0, N);
+ * n_index <= N; the last chunk may be shorter).  Peers not listed are left
+ * alone.  This is the group-average step of Alg. 1 for any group assignment,
+ * e.g. one produced by a matchmaking layer above this library. */
+int moshpit_grouped_round(moshpit_ctx *h, const int32_t *index_host, int64_t n_index, int32_t group_size,
+                          const uint8_t *alive_host);
+
 /* Measurement aids (no counterpart in the paper).
  *
  * moshpit_set_tuning overrides the launch shape of the averaging kernel:

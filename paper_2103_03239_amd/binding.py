@@ -23,7 +23,7 @@ RUN_DEFAULT, RUN_FUSED = 0, 1
 EXPORTS = [
     "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",
     "moshpit_run", "moshpit_dist_to_mean", "moshpit_dist_to_mean_subset", "moshpit_group_keys", "moshpit_schedule_mask",
-    "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
+    "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
 ]
 
 
@@ -67,6 +67,9 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_dist_to_mean_subset.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.moshpit_group_keys.argtypes = [vp, i64, vp]
     lib.moshpit_schedule_mask.argtypes = [vp, ctypes.POINTER(_CSchedule), i64, i32, vp]
+    lib.moshpit_random_groups_round.argtypes = [vp, i64, ctypes.c_uint64, i32, vp]
+    lib.moshpit_random_permutation.argtypes = [vp, i64, ctypes.c_uint64, vp]
+    lib.moshpit_grouped_round.argtypes = [vp, vp, i64, i32, vp]
     lib.moshpit_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.moshpit_copy_probe.argtypes = [vp, vp, i64, vp]
     lib.moshpit_sync.argtypes = [vp]
@@ -205,6 +208,29 @@ class Moshpit:
         self._check(rc, "schedule_mask")
         del keep
         return masks
+
+    def _alive_ptr(self, alive):
+        if alive is None:
+            return None, None
+        a = np.ascontiguousarray(alive, dtype=np.uint8)
+        if a.shape != (self.N,):
+            raise ValueError("alive mask must have shape (N,)")
+        return a, a.ctypes.data
+
+    def random_groups_round(self, t: int, seed: int, group_size: int, alive=None) -> None:
+        keep, ptr = self._alive_ptr(alive)
+        self._check(self._lib.moshpit_random_groups_round(self._h, t, seed, group_size, ptr), "random_groups_round")
+
+    def random_permutation(self, t: int, seed: int) -> np.ndarray:
+        perm = np.empty(self.N, dtype=np.int32)
+        self._check(self._lib.moshpit_random_permutation(self._h, t, seed, perm.ctypes.data), "random_permutation")
+        return perm
+
+    def grouped_round(self, index, group_size: int, alive=None) -> None:
+        idx = np.ascontiguousarray(index, dtype=np.int32)
+        keep, ptr = self._alive_ptr(alive)
+        self._check(self._lib.moshpit_grouped_round(self._h, idx.ctypes.data, len(idx), group_size, ptr),
+                    "grouped_round")
 
     def set_tuning(self, cols: int = 0, unroll: int = 0, nontemporal: int = -1, block: int = 0,
                    waves_per_cu: int = 0) -> None:

@@ -23,6 +23,7 @@ struct moshpit_ctx {
 
     uint8_t *d_round_mask = nullptr;   // N bytes, for moshpit_round(host mask)
     uint8_t *d_present = nullptr;      // N bytes, for moshpit_dist_to_mean_subset
+    int32_t *d_perm = nullptr;         // N, peer list of the list-based rounds
     uint8_t *d_masks = nullptr;        // mask_rounds_cap * N bytes, for runs
     int64_t mask_rounds_cap = 0;
     int32_t *d_keys = nullptr;         // N
@@ -202,6 +203,7 @@ int moshpit_destroy(moshpit_ctx *h)
     for (hipEvent_t ev : h->events) (void)hipEventDestroy(ev);
     if (h->d_round_mask) (void)hipFree(h->d_round_mask);
     if (h->d_present) (void)hipFree(h->d_present);
+    if (h->d_perm) (void)hipFree(h->d_perm);
     if (h->d_masks) (void)hipFree(h->d_masks);
     if (h->d_keys) (void)hipFree(h->d_keys);
     if (h->d_partials) (void)hipFree(h->d_partials);
@@ -372,6 +374,70 @@ int moshpit_dist_to_mean_subset(moshpit_ctx *h, const uint8_t *present_host, dou
     HIP_TRY(h, hipMemcpyAsync(out_host, h->d_dist, sizeof(double), hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return MOSHPIT_OK;
+}
+
+namespace {
+// Queue one round over consecutive chunks of `group_size` entries of a device peer list.
+int queue_list_round(moshpit_ctx *h, const int32_t *index_dev, int64_t n_index, int32_t group_size,
+                     const uint8_t *alive_host)
+{
+    const uint8_t *alive_dev = nullptr;
+    if (alive_host) {
+        HIP_TRY(h, hipMemcpyAsync(h->d_round_mask, alive_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice,
+                                  h->stream));
+        alive_dev = h->d_round_mask;
+    }
+    RoundGeom geom{h->N, group_size, 1, index_dev, n_index};
+    HIP_TRY(h, launch_group_mean(h->X, h->dtype, h->P, h->row_stride, geom, alive_dev, h->tune, h->stream));
+    return MOSHPIT_OK;
+}
+}  // namespace
+
+int moshpit_random_permutation(moshpit_ctx *h, int64_t t, uint64_t seed, int32_t *perm_host)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    if (t < 0 || !perm_host) return fail(h, MOSHPIT_EINVAL, "bad round index or NULL output");
+    if (h->N > 65536) return fail(h, MOSHPIT_EINVAL, "random groups support at most 65536 peers");
+    HIP_TRY(h, launch_random_permutation(seed, t, h->N, h->d_keys, h->stream));
+    HIP_TRY(h, hipMemcpyAsync(perm_host, h->d_keys, sizeof(int32_t) * static_cast<size_t>(h->N),
+                              hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return MOSHPIT_OK;
+}
+
+int moshpit_random_groups_round(moshpit_ctx *h, int64_t t, uint64_t seed, int32_t group_size,
+                                const uint8_t *alive_host)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
+    if (group_size < 1 || group_size > 64) return fail(h, MOSHPIT_EINVAL, "group_size must be in [1, 64]");
+    if (h->N > 65536) return fail(h, MOSHPIT_EINVAL, "random groups support at most 65536 peers");
+    if (!h->d_perm) HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_perm), sizeof(int32_t) * static_cast<size_t>(h->N)));
+    HIP_TRY(h, launch_random_permutation(seed, t, h->N, h->d_perm, h->stream));
+    return queue_list_round(h, h->d_perm, h->N, group_size, alive_host);
+}
+
+int moshpit_grouped_round(moshpit_ctx *h, const int32_t *index_host, int64_t n_index, int32_t group_size,
+                          const uint8_t *alive_host)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (!index_host || n_index < 0 || n_index > h->N)
+        return fail(h, MOSHPIT_EINVAL, "peer list is NULL or longer than N");
+    if (group_size < 1 || group_size > 64) return fail(h, MOSHPIT_EINVAL, "group_size must be in [1, 64]");
+    std::vector<uint8_t> seen(static_cast<size_t>(h->N), 0);
+    for (int64_t q = 0; q < n_index; ++q) {
+        const int32_t r = index_host[q];
+        if (r < 0 || r >= h->N) return fail(h, MOSHPIT_EINVAL, "peer list entry %lld is out of range", (long long)q);
+        if (seen[r]) return fail(h, MOSHPIT_EINVAL, "peer %d is listed twice", r);
+        seen[r] = 1;
+    }
+    if (n_index == 0) return MOSHPIT_OK;
+    if (!h->d_perm) HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_perm), sizeof(int32_t) * static_cast<size_t>(h->N)));
+    HIP_TRY(h, hipMemcpyAsync(h->d_perm, index_host, sizeof(int32_t) * static_cast<size_t>(n_index),
+                              hipMemcpyHostToDevice, h->stream));
+    return queue_list_round(h, h->d_perm, n_index, group_size, alive_host);
 }
 
 int moshpit_group_keys(moshpit_ctx *h, int64_t t, int32_t *keys_host)

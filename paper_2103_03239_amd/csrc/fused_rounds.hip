@@ -218,7 +218,6 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
     for (int32_t lr = tid; lr < p.rows; lr += kThreads) rowoff[lr] = global_row(p, 0, lr) * p.row_bytes;
 
     const int32_t Wv = p.Wb / 16;
-    const int32_t total_vec = p.rows * Wv;
     const int32_t W = p.Wb / static_cast<int32_t>(sizeof(elem_t));     // columns of a full tile
 
     // Participant bitmaps of every (round, group) of a sub-grid and per-row

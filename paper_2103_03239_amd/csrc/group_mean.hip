@@ -111,11 +111,14 @@ template <bool NT, typename T> __device__ __forceinline__ void store_vec(T *p, c
 // row_bytes    distance between rows in bytes
 // nvec         vectors of VE elements per row covered by this launch
 // tiles        ceil(nvec / (blockDim.x * COLS))
-// work_items   (N / M) * tiles
-template <int DT, int VE, int COLS, int U, bool NT>
+// work_items   groups * tiles
+// IDX          groups are consecutive chunks of M entries of the peer list
+//              index[0..n_index) (e.g. a random permutation) instead of grid lines
+template <int DT, int VE, int COLS, int U, bool NT, bool IDX>
 __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t row_bytes, int64_t nvec,
                                                             const uint8_t *__restrict__ alive, int32_t M,
-                                                            int64_t S, int64_t tiles, int64_t work_items)
+                                                            int64_t S, int64_t tiles, int64_t work_items,
+                                                            const int32_t *__restrict__ index, int64_t n_index)
 {
     typedef Vec<DT, VE> V;
     typedef typename V::mem_t mem_t;
@@ -126,10 +129,17 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
     for (int64_t w = blockIdx.x; w < work_items; w += gridDim.x) {
         const int64_t g = w / tiles;
         const int64_t tile = w - g * tiles;
-        const int64_t base = (g / S) * S * M + (g % S);
-
+        int64_t base = 0;
+        int32_t my_row = -1;                         // IDX: the row of position `lane`
         bool takes_part = false;
-        if (lane < M) takes_part = (alive == nullptr) || (alive[base + static_cast<int64_t>(lane) * S] != 0);
+        if constexpr (IDX) {
+            const int64_t pos = g * M + lane;
+            if (lane < M && pos < n_index) my_row = index[pos];
+            takes_part = my_row >= 0 && ((alive == nullptr) || (alive[my_row] != 0));
+        } else {
+            base = (g / S) * S * M + (g % S);
+            if (lane < M) takes_part = (alive == nullptr) || (alive[base + static_cast<int64_t>(lane) * S] != 0);
+        }
         const uint64_t live = __ballot(takes_part);
         const int cnt = __popcll(live);
         if (cnt < 2) continue;                       // nothing to average: rows stay as they are
@@ -141,6 +151,13 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
 
         char *gbase = X + base * row_bytes + v0 * static_cast<int64_t>(sizeof(mem_t));
         const int64_t jstep = S * row_bytes;
+        // address of this lane's first vector in the row of position j (j is wave-uniform)
+        auto row_ptr = [&](int j) -> char * {
+            if constexpr (IDX)
+                return gbase + static_cast<int64_t>(__builtin_amdgcn_readlane(my_row, j)) * row_bytes;
+            else
+                return gbase + j * jstep;
+        };
 
         float acc[COLS][NE];
 #pragma unroll
@@ -161,7 +178,7 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
 #pragma unroll
                 for (int c = 0; c < COLS; ++c) buf[u][c] = V::zero();
                 if ((bits >> u) & 1ull) {
-                    const mem_t *src = reinterpret_cast<const mem_t *>(gbase + (j0 + u) * jstep);
+                    const mem_t *src = reinterpret_cast<const mem_t *>(row_ptr(j0 + u));
 #pragma unroll
                     for (int c = 0; c < COLS; ++c)
                         if (in_row[c]) buf[u][c] = load_vec<NT>(src + c * kBlock);
@@ -196,7 +213,7 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
         while (rem != 0) {
             const int j = __builtin_ctzll(rem);
             rem &= rem - 1;
-            mem_t *dst = reinterpret_cast<mem_t *>(gbase + j * jstep);
+            mem_t *dst = reinterpret_cast<mem_t *>(row_ptr(j));
 #pragma unroll
             for (int c = 0; c < COLS; ++c)
                 if (in_row[c]) store_vec<NT>(dst + c * kBlock, mean[c]);
@@ -207,16 +224,18 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
 // The kernel uses no LDS.  The dynamic-LDS size of the launch is only a
 // throttle: a block that reserves lds bytes lets floor(160 KiB / lds) blocks
 // share a compute unit, which bounds the number of row loads in flight.
-template <int DT, int VE, int COLS, int U, bool NT>
+template <int DT, int VE, int COLS, int U, bool NT, bool IDX = false>
 hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *alive, const RoundGeom &geom,
                       int block, int waves_per_cu, hipStream_t stream)
 {
     if (nvec <= 0) return hipSuccess;
     const int64_t per_tile = static_cast<int64_t>(block) * COLS;
     const int64_t tiles = (nvec + per_tile - 1) / per_tile;
-    const int64_t work = (geom.N / geom.M) * tiles;
+    const int64_t groups = IDX ? (geom.n_index + geom.M - 1) / geom.M : geom.N / geom.M;
+    const int64_t work = groups * tiles;
+    if (work <= 0) return hipSuccess;
     const int64_t grid = work < 0x7fffffffLL ? work : 0x7fffffffLL;
-    auto kernel = group_mean_kernel<DT, VE, COLS, U, NT>;
+    auto kernel = group_mean_kernel<DT, VE, COLS, U, NT, IDX>;
     size_t lds = 0;
     if (waves_per_cu > 0 && waves_per_cu < 32) {
         int blocks_per_cu = waves_per_cu / (block / 64);
@@ -231,7 +250,8 @@ hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *a
         }
     }
     kernel<<<dim3(static_cast<uint32_t>(grid)), dim3(block), lds, stream>>>(X, row_bytes, nvec, alive, geom.M,
-                                                                            geom.S, tiles, work);
+                                                                            geom.S, tiles, work, geom.index,
+                                                                            geom.n_index);
     return hipGetLastError();
 }
 
@@ -239,6 +259,14 @@ template <int DT, int VE>
 hipError_t launch_shape(int cols, int unroll, bool nt, char *X, int64_t row_bytes, int64_t nvec,
                         const uint8_t *alive, const RoundGeom &geom, int block, int wpc, hipStream_t stream)
 {
+    if (geom.index != nullptr) {
+        // peer-list groups: the default shapes only, streaming accesses
+        if (cols == 1 && unroll == 16) return launch_one<DT, VE, 1, 16, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        if (cols == 2 && unroll == 8) return launch_one<DT, VE, 2, 8, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        if (cols == 4 && unroll == 4) return launch_one<DT, VE, 4, 4, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        if (cols == 4 && unroll == 2) return launch_one<DT, VE, 4, 2, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        return hipErrorInvalidValue;
+    }
 #define MOSHPIT_CASE(C, UU)                                                                          \
     if (cols == C && unroll == UU)                                                                   \
         return nt ? launch_one<DT, VE, C, UU, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream)   \
@@ -276,7 +304,7 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     // about 20-24 MiB in flight on the chip.  More than that and the HBM
     // controllers see too many open pages; less and latency is not covered.
     int cols = tune.cols, unroll = tune.unroll;
-    if (cols <= 0 || unroll <= 0) {
+    if (cols <= 0 || unroll <= 0 || geom.index != nullptr) {
         if (geom.M > 8) { unroll = 16; cols = 1; }
         else if (geom.M > 4) { unroll = 8; cols = 2; }
         else if (geom.M > 2) { unroll = 4; cols = 4; }
@@ -302,8 +330,12 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     }
     if (tail0 < P) {
         char *tbase = base + tail0 * esize;
-        e = dtype == 0 ? launch_one<0, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream)
-                       : launch_one<1, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream);
+        if (geom.index != nullptr)
+            e = dtype == 0 ? launch_one<0, 1, 1, 8, false, true>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream)
+                           : launch_one<1, 1, 1, 8, false, true>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream);
+        else
+            e = dtype == 0 ? launch_one<0, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream)
+                           : launch_one<1, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream);
     }
     return e;
 }

@@ -22,10 +22,14 @@ struct MeanTuning {
 
 // Geometry of one round: group g (0 <= g < N/M) owns rows base(g) + j*S,
 // j = 0..M-1, with S = M^(t mod d) and base(g) = (g / S) * S * M + g % S.
+// With index != nullptr the groups are instead consecutive chunks of M entries of
+// the peer list index[0..n_index) (device memory), the last chunk possibly short.
 struct RoundGeom {
     int64_t N;
     int32_t M;
     int64_t S;
+    const int32_t *index = nullptr;
+    int64_t n_index = 0;
 };
 
 // Queue one averaging round on `stream`.  X: device, row-major, `P` valid
@@ -47,6 +51,10 @@ hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, i
 // Queue the failure-schedule generator: masks[r][i] (device, rounds*N bytes).
 hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down, int64_t N, int64_t t0,
                            int rounds, uint8_t *masks, hipStream_t stream);
+
+// Queue the random-permutation kernel: perm[r] = peer of rank r when the peers
+// are ordered by their 64-bit key of (seed, t), ties by index (device, N int32).
+hipError_t launch_random_permutation(uint64_t seed, int64_t t, int64_t N, int32_t *perm, hipStream_t stream);
 
 // Queue the group-key kernel: keys[i] (device, N int32) for axis a, S = M^a.
 hipError_t launch_group_keys(int64_t N, int32_t M, int64_t S, int32_t *keys, hipStream_t stream);

@@ -48,6 +48,30 @@ __global__ __launch_bounds__(256) void schedule_kernel(int kind, uint32_t thresh
     }
 }
 
+// Random permutation for the random-group scheme analysed in Thm 3.2 (its proof
+// in App. C.3 draws a permutation and cuts it into consecutive groups).  Peers
+// are ordered by key(seed,t,i) = mix(mix(seed + 0xD1B54A32D192ED03*(t+1)) ^ i),
+// ties by index; thread i counts its rank against all peers (N is at most a
+// few thousand) and writes perm[rank] = i.
+__device__ __forceinline__ uint64_t order_key(uint64_t seed, int64_t t, int64_t i)
+{
+    return mix64(mix64(seed + 0xD1B54A32D192ED03ull * static_cast<uint64_t>(t + 1)) ^ static_cast<uint64_t>(i));
+}
+
+__global__ __launch_bounds__(256) void random_permutation_kernel(uint64_t seed, int64_t t, int64_t N,
+                                                                 int32_t *__restrict__ perm)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= N) return;
+    const uint64_t ki = order_key(seed, t, i);
+    int64_t rank = 0;
+    for (int64_t j = 0; j < N; ++j) {
+        const uint64_t kj = order_key(seed, t, j);
+        rank += (kj < ki || (kj == ki && j < i)) ? 1 : 0;
+    }
+    perm[rank] = static_cast<int32_t>(i);
+}
+
 // key(i) = the base-M number formed by the digits of i other than digit a,
 // i.e. floor(i / (S*M)) * S + i mod S with S = M^a.
 __global__ __launch_bounds__(256) void group_keys_kernel(int64_t N, int32_t M, int64_t S, int32_t *__restrict__ keys)
@@ -65,6 +89,14 @@ hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down
     if (N <= 0 || rounds <= 0) return hipSuccess;
     const uint32_t blocks = static_cast<uint32_t>((N + 255) / 256);
     schedule_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(kind, threshold, seed, down, N, t0, rounds, masks);
+    return hipGetLastError();
+}
+
+hipError_t launch_random_permutation(uint64_t seed, int64_t t, int64_t N, int32_t *perm, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    const uint32_t blocks = static_cast<uint32_t>((N + 255) / 256);
+    random_permutation_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(seed, t, N, perm);
     return hipGetLastError();
 }
 

@@ -356,3 +356,83 @@ def test_partly_filled_grid(M, d, n_present, dtype, P, p):
     X0 = inputs.make_state(w, DEV)
     empty = torch.from_numpy(present == 0).to(DEV)
     assert torch.equal(X[empty], X0[empty])
+
+
+# --------------------------------------------------------------------------
+# averaging in random groups (the simplified scheme of Thm 3.2) and list-based rounds
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N", [16, 100, 1024, 4096])
+def test_random_permutation_bit_exact(N):
+    # the permutation only depends on N: use any handle with that many peers
+    shapes = {16: (4, 2), 100: (10, 2), 1024: (32, 2), 4096: (16, 3)}
+    M, d = shapes[N]
+    with binding.Moshpit(N, 8, M, d, 0) as m:
+        for t, seed in ((0, 1), (3, 2**63 + 5), (7, 12345)):
+            say(f"perm N={N} t={t} seed={seed}")
+            assert np.array_equal(m.random_permutation(t, seed), orc.random_permutation(seed, t, N))
+
+
+@pytest.mark.parametrize("M,d,P,dtype,gs,p", [(32, 2, 3_000, 0, 32, 0.0), (32, 2, 1_001, 0, 7, 0.2),
+                                              (16, 3, 520, 1, 16, 0.1), (10, 2, 4_096, 0, 64, 0.3),
+                                              (4, 2, 999, 1, 2, 0.25), (3, 3, 64, 0, 5, 0.0), (4, 3, 5_000, 0, 1, 0.0)])
+def test_random_groups_rounds(M, d, P, dtype, gs, p):
+    N, rounds, seed = M ** d, 4, 99
+    w = inputs.Workload("random-groups", N, M, d, P, dtype, "peer_offset", 1, p, 0, rounds, 5 + P, 6 + gs)
+    say(f"random groups {w} group_size={gs}")
+    stride = P + (8 - P % 8) % 8
+    X = inputs.make_state(w, DEV, row_stride=stride)
+    ref = to_f64(X).copy()
+    masks = orc.schedule_masks(1, p, w.mask_seed, 0, N, 0, rounds)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(X)
+        for t in range(rounds):
+            m.random_groups_round(t, seed, gs, masks[t] if p > 0 else None)
+            orc.random_groups_round(ref, seed, t, gs, masks[t] if p > 0 else None)
+        m.sync()
+        assert_state_close(to_f64(X), ref, TOL[dtype], w.name)
+        d_got, d_want = m.dist_to_mean(), orc.dist_to_mean(ref)
+        assert abs(d_got - d_want) <= TOL[dtype] * d_want + dist_floor(P, dtype, 1.0)
+
+
+def test_random_groups_contraction_rate():
+    """One round of random groups of 32 among 1024 peers shrinks the distortion
+    by (r-1)/(N-1) = 31/1023 in expectation (Thm 3.2, whose printed rate
+    31/1024 + 32/1024^2 is the same to 1e-6); with 8192 iid columns a single
+    permutation already averages to well within 2 %."""
+    N, P, gs = 1024, 8192, 32
+    w = inputs.Workload("rate", N, 32, 2, P, 0, "normal", 0, 0.0, 0, 1, 31, 32)
+    X = inputs.make_state(w, DEV)
+    with binding.Moshpit(N, P, 32, 2, 0) as m:
+        m.bind_state(X)
+        d0 = m.dist_to_mean()
+        m.random_groups_round(0, 7, gs)
+        d1 = m.dist_to_mean()
+    rate = 31 / 1023
+    assert abs(d1 / d0 - rate) <= 0.02 * rate, (d1 / d0, rate)
+
+
+def test_grouped_round_with_caller_groups():
+    N, P = 64, 2_000
+    w = inputs.Workload("lists", N, 8, 2, P, 0, "normal", 0, 0.0, 0, 1, 41, 42)
+    X = inputs.make_state(w, DEV)
+    X0 = X.clone()
+    ref = to_f64(X).copy()
+    rng = np.random.default_rng(8)
+    index = rng.permutation(N)[:50]                      # 14 peers are not listed at all
+    alive = (rng.random(N) > 0.2).astype(np.uint8)
+    with binding.Moshpit(N, P, 8, 2, 0) as m:
+        m.bind_state(X)
+        m.grouped_round(index, 6, alive)
+        orc.grouped_round(ref, index, 6, alive)
+        m.sync()
+        assert_state_close(to_f64(X), ref, 1e-6, "caller groups")
+        untouched = np.setdiff1d(np.arange(N), index[alive[index] == 1])
+        assert torch.equal(X[untouched], X0[untouched])
+        m.grouped_round(np.zeros(0, np.int32), 4)       # empty list: nothing happens
+        with pytest.raises(binding.MoshpitError):
+            m.grouped_round([1, 2, 2], 2)               # a peer listed twice
+        with pytest.raises(binding.MoshpitError):
+            m.grouped_round([1, 64], 2)                 # out of range
+        with pytest.raises(binding.MoshpitError):
+            m.random_groups_round(0, 1, 65)
