@@ -286,6 +286,30 @@ int oracle_schedule_masks(int32_t kind, double p, uint64_t seed, int32_t down,
     return 0;
 }
 
+/* ---- failure during the all-reduce: the whole group skips ---------------- */
+
+/*
+ * Sec. 3.1 names a second failure behaviour: a peer that fails during the
+ * all-reduce makes its groupmates skip that round.  As a filter on the masks:
+ * effective[i] = 1 iff every member of i's round-t group is alive (on a full
+ * grid), else 0 for the whole group.  A round run with `effective` is the
+ * round with group-skip semantics.
+ */
+int oracle_skip_filter(int64_t N, int32_t M, int32_t d, int64_t t, const uint8_t *alive, uint8_t *effective)
+{
+    int64_t *gid = (int64_t *)malloc(sizeof(int64_t) * (size_t)(N > 0 ? N : 1));
+    if (!gid) return -2;
+    if (oracle_group_ids(N, M, d, t, gid) != 0) { free(gid); return -1; }
+    for (int64_t i = 0; i < N; ++i) {
+        int complete = 1;
+        for (int64_t j = 0; j < N; ++j)
+            if (gid[j] == gid[i] && alive[j] == 0) complete = 0;
+        effective[i] = (uint8_t)complete;
+    }
+    free(gid);
+    return 0;
+}
+
 /* ---- averaging in random groups ---------------------------------------- */
 
 /*

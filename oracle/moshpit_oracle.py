@@ -54,6 +54,7 @@ def _load():
         lib.oracle_dist_to_mean_subset.argtypes = [_ptr, _i64, _i64, _i64, _ptr]
         lib.oracle_dist_to_mean_subset.restype = _f64
         lib.oracle_schedule_masks.argtypes = [_i32, _f64, _u64, _i32, _i64, _i64, _i32, _ptr]
+        lib.oracle_skip_filter.argtypes = [_i64, _i32, _i32, _i64, _ptr, _ptr]
         lib.oracle_random_permutation.argtypes = [_u64, _i64, _i64, _ptr]
         lib.oracle_grouped_round.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _i64, _i32, _ptr]
         lib.oracle_random_groups_round.argtypes = [_ptr, _i64, _i64, _i64, _u64, _i64, _i32, _ptr]
@@ -134,6 +135,14 @@ def schedule_masks(kind: int, p: float, seed: int, down: int, N: int, t0: int, r
     _check(_load().oracle_schedule_masks(kind, float(p), seed, down, N, t0, rounds,
                                          masks.ctypes.data), "schedule_masks")
     return masks
+
+
+def skip_filter(N: int, M: int, d: int, t: int, alive) -> np.ndarray:
+    """Masks of the group-skip behaviour: a group with a failed member sits the round out."""
+    a = np.ascontiguousarray(alive, dtype=np.uint8)
+    out = np.empty(N, dtype=np.uint8)
+    _check(_load().oracle_skip_filter(N, M, d, t, a.ctypes.data, out.ctypes.data), "skip_filter")
+    return out
 
 
 def random_permutation(seed: int, t: int, N: int) -> np.ndarray:

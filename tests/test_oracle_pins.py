@@ -320,6 +320,60 @@ def test_dist_subset_is_numpy_definition():
 
 
 # --------------------------------------------------------------------------
+# group-skip failure behaviour (Sec. 3.1)
+# --------------------------------------------------------------------------
+
+def test_skip_filter_all_masks():
+    """From first principles in Python: a peer takes part iff nobody in its
+    group failed.  All 2^N masks on 2x2, 3x3 and 2x2x2 grids, every axis."""
+    for M, d in ((2, 2), (3, 2), (2, 3)):
+        N = M ** d
+        for bits in itertools.product([0, 1], repeat=N):
+            alive = np.array(bits, dtype=np.uint8)
+            for t in range(d):
+                a = t % d
+                want = np.zeros(N, dtype=np.uint8)
+                for i in range(N):
+                    mates = [j for j in range(N)
+                             if all((j // M ** q) % M == (i // M ** q) % M for q in range(d) if q != a)]
+                    want[i] = int(all(alive[j] for j in mates))
+                assert np.array_equal(orc.skip_filter(N, M, d, t, alive), want)
+
+
+def test_skip_semantics_properties():
+    """With group-skip every group either averages completely or not at all:
+    the global sum is preserved, the distortion never grows, it converges no
+    faster than the survivors-average behaviour, and without failures both
+    behaviours coincide."""
+    rng = np.random.default_rng(21)
+    M, d, N = 8, 2, 64
+    X0 = rng.normal(size=(N, 3))
+    masks = orc.schedule_masks(1, 0.05, 5, 0, N, 0, 12)
+    A, B = X0.copy(), X0.copy()
+    prev = orc.dist_to_mean(B)
+    for t in range(12):
+        eff = orc.skip_filter(N, M, d, t, masks[t])
+        assert (eff <= masks[t]).all()
+        before = B.copy()
+        orc.round_(A, M, d, t, masks[t])
+        orc.round_(B, M, d, t, eff)
+        gid = orc.group_ids(N, M, d, t)
+        for lead in np.unique(gid):
+            grp = gid == lead
+            if masks[t][grp].all():
+                assert np.allclose(B[grp], before[grp].mean(axis=0), atol=1e-15, rtol=0)
+            else:
+                assert np.array_equal(B[grp], before[grp])
+        assert np.allclose(B.sum(axis=0), X0.sum(axis=0), atol=1e-12, rtol=0)
+        cur = orc.dist_to_mean(B)
+        assert cur <= prev + 1e-15
+        prev = cur
+    assert orc.dist_to_mean(B) >= orc.dist_to_mean(A)
+    ones = np.ones(N, dtype=np.uint8)
+    assert np.array_equal(orc.skip_filter(N, M, d, 1, ones), ones)
+
+
+# --------------------------------------------------------------------------
 # averaging in random groups: the exact contraction rate of Thm 3.2
 # --------------------------------------------------------------------------
 
