@@ -74,6 +74,12 @@ typedef struct {
     double   p;                     /* failure probability in [0,1]               */
     uint64_t seed;
     const uint8_t *explicit_masks;  /* kind EXPLICIT: host, [rounds][N], 1=alive  */
+    int32_t  group_skip;            /* 0: the members that are present average
+                                       (App. E: a group is formed from whoever
+                                       remains); 1: a group with an absent
+                                       member sits the round out (Sec. 3.1: a
+                                       failure during the all-reduce makes the
+                                       groupmates skip the round)               */
 } moshpit_schedule;
 
 /* Flags of moshpit_run.

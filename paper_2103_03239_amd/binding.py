@@ -33,7 +33,7 @@ class MoshpitError(RuntimeError):
 
 class _CSchedule(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("down_rounds", ctypes.c_int32), ("p", ctypes.c_double),
-                ("seed", ctypes.c_uint64), ("explicit_masks", ctypes.c_void_p)]
+                ("seed", ctypes.c_uint64), ("explicit_masks", ctypes.c_void_p), ("group_skip", ctypes.c_int32)]
 
 
 @dataclass
@@ -43,6 +43,7 @@ class Schedule:
     seed: int = 0
     down_rounds: int = 0
     explicit_masks: np.ndarray | None = None      # uint8 [rounds, N] for SCHED_EXPLICIT
+    group_skip: bool = False                      # a group with an absent member skips the round
 
 
 _lib = None
@@ -92,7 +93,7 @@ def _c_schedule(s: Schedule | None, rounds: int, N: int):
         if keep.shape != (rounds, N):
             raise ValueError("explicit masks must have shape (rounds, N)")
         ptr = keep.ctypes.data
-    return _CSchedule(s.kind, s.down_rounds, float(s.p), s.seed, ptr), keep
+    return _CSchedule(s.kind, s.down_rounds, float(s.p), s.seed, ptr, 1 if s.group_skip else 0), keep
 
 
 class Moshpit:

@@ -135,13 +135,15 @@ int queue_masks(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t r
     if (s && s->kind == MOSHPIT_SCHED_EXPLICIT) {
         HIP_TRY(h, hipMemcpyAsync(h->d_masks, s->explicit_masks, static_cast<size_t>(rounds) * h->N,
                                   hipMemcpyHostToDevice, h->stream));
-        return MOSHPIT_OK;
+    } else {
+        const int kind = s ? s->kind : MOSHPIT_SCHED_NONE;
+        const double p = s ? s->p : 0.0;
+        const uint32_t threshold = static_cast<uint32_t>(std::floor(p * 16777216.0));
+        HIP_TRY(h, launch_schedule(kind, threshold, s ? s->seed : 0, s ? s->down_rounds : 0, h->N, t0, rounds,
+                                   h->d_masks, h->stream));
     }
-    const int kind = s ? s->kind : MOSHPIT_SCHED_NONE;
-    const double p = s ? s->p : 0.0;
-    const uint32_t threshold = static_cast<uint32_t>(std::floor(p * 16777216.0));
-    HIP_TRY(h, launch_schedule(kind, threshold, s ? s->seed : 0, s ? s->down_rounds : 0, h->N, t0, rounds,
-                               h->d_masks, h->stream));
+    if (s && s->group_skip)
+        HIP_TRY(h, launch_skip_filter(h->d_masks, h->N, h->M, h->d, t0, rounds, h->stream));
     return MOSHPIT_OK;
 }
 

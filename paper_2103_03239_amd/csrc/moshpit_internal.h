@@ -52,6 +52,10 @@ hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, i
 hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down, int64_t N, int64_t t0,
                            int rounds, uint8_t *masks, hipStream_t stream);
 
+// Queue the group-skip filter on masks[rounds][N] (device, in place) for rounds t0..
+hipError_t launch_skip_filter(uint8_t *masks, int64_t N, int32_t M, int32_t d, int64_t t0, int rounds,
+                              hipStream_t stream);
+
 // Queue the random-permutation kernel: perm[r] = peer of rank r when the peers
 // are ordered by their 64-bit key of (seed, t), ties by index (device, N int32).
 hipError_t launch_random_permutation(uint64_t seed, int64_t t, int64_t N, int32_t *perm, hipStream_t stream);

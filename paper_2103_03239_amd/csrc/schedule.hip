@@ -48,6 +48,24 @@ __global__ __launch_bounds__(256) void schedule_kernel(int kind, uint32_t thresh
     }
 }
 
+// Group-skip behaviour (Sec. 3.1: a peer that fails during the all-reduce makes
+// its groupmates skip the round).  One wave per (round, group): if any member
+// of the group is absent, every member's byte is cleared.  In place: a group's
+// bytes belong to that group alone.
+__global__ __launch_bounds__(64) void skip_filter_kernel(uint8_t *__restrict__ masks, int64_t N, int32_t M, int32_t d,
+                                                          int64_t t0, int64_t groups)
+{
+    const int64_t r = blockIdx.x / groups;
+    const int64_t g = blockIdx.x - r * groups;
+    int64_t S = 1;
+    for (int64_t q = 0; q < (t0 + r) % d; ++q) S *= M;
+    const int64_t base = (g / S) * S * M + (g % S);
+    const int lane = threadIdx.x;
+    uint8_t *mine = masks + r * N + base + static_cast<int64_t>(lane) * S;
+    const bool absent = lane < M && *mine == 0;
+    if (__ballot(absent) != 0 && lane < M) *mine = 0;
+}
+
 // Random permutation for the random-group scheme analysed in Thm 3.2 (its proof
 // in App. C.3 draws a permutation and cuts it into consecutive groups).  Peers
 // are ordered by key(seed,t,i) = mix(mix(seed + 0xD1B54A32D192ED03*(t+1)) ^ i),
@@ -89,6 +107,17 @@ hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down
     if (N <= 0 || rounds <= 0) return hipSuccess;
     const uint32_t blocks = static_cast<uint32_t>((N + 255) / 256);
     schedule_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(kind, threshold, seed, down, N, t0, rounds, masks);
+    return hipGetLastError();
+}
+
+hipError_t launch_skip_filter(uint8_t *masks, int64_t N, int32_t M, int32_t d, int64_t t0, int rounds,
+                              hipStream_t stream)
+{
+    const int64_t groups = N / M;
+    const int64_t blocks = groups * rounds;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    skip_filter_kernel<<<dim3(static_cast<uint32_t>(blocks)), dim3(64), 0, stream>>>(masks, N, M, d, t0, groups);
     return hipGetLastError();
 }
 

@@ -436,3 +436,30 @@ def test_grouped_round_with_caller_groups():
             m.grouped_round([1, 64], 2)                 # out of range
         with pytest.raises(binding.MoshpitError):
             m.random_groups_round(0, 1, 65)
+
+
+# --------------------------------------------------------------------------
+# group-skip failure behaviour
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,d,P,dtype,p,fused", [(16, 2, 2_000, 0, 0.02, 0), (4, 3, 1_000, 1, 0.1, 0),
+                                                  (32, 2, 520, 0, 0.01, 1), (3, 3, 100, 0, 0.05, 1)])
+def test_group_skip_schedule(M, d, P, dtype, p, fused):
+    N, rounds = M ** d, 6
+    w = inputs.Workload("skip", N, M, d, P, dtype, "normal", 1, p, 0, rounds, 51, 52)
+    say(f"group skip {w} fused={fused}")
+    X = inputs.make_state(w, DEV, row_stride=P + (8 - P % 8) % 8)
+    ref = to_f64(X).copy()
+    raw = orc.schedule_masks(1, p, 52, 0, N, 0, rounds)
+    eff = np.stack([orc.skip_filter(N, M, d, t, raw[t]) for t in range(rounds)])
+    orc.run(ref, M, d, 0, rounds, eff)
+    sched = binding.Schedule(kind=1, p=p, seed=52, group_skip=True)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(X)
+        assert np.array_equal(m.schedule_mask(sched, 0, rounds), eff)
+        m.run(0, rounds, sched, flags=binding.RUN_FUSED if fused else 0)
+        m.sync()
+        # explicit masks go through the same filter
+        sched2 = binding.Schedule(kind=binding.SCHED_EXPLICIT, explicit_masks=raw, group_skip=True)
+        assert np.array_equal(m.schedule_mask(sched2, 0, rounds), eff)
+    assert_state_close(to_f64(X), ref, TOL[dtype], "group skip")
