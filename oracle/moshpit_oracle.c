@@ -391,6 +391,35 @@ int oracle_random_groups_round(double *X, int64_t N, int64_t W, int64_t ld, uint
     return rc;
 }
 
+/* ---- Moshpit SGD step (Alg. 2) ------------------------------------------ */
+
+/*
+ * Local part of an iteration of Alg. 2: every peer of P_{k+1} (alive != 0;
+ * NULL = all) moves to theta_i - gamma * g_i.  G is row-major [N][ldg].
+ */
+int oracle_local_step(double *X, const double *G, int64_t N, int64_t W, int64_t ld, int64_t ldg, double gamma,
+                      const uint8_t *alive)
+{
+    for (int64_t i = 0; i < N; ++i) {
+        if (alive != NULL && alive[i] == 0) continue;
+        for (int64_t c = 0; c < W; ++c) X[i * ld + c] = X[i * ld + c] - gamma * G[i * ldg + c];
+    }
+    return 0;
+}
+
+/*
+ * Communication iteration of Alg. 2 with one Moshpit round:
+ * theta_i <- average over i's round-t group of (theta_j - gamma * g_j), the
+ * group being formed from the peers of P_{k+1}.
+ */
+int oracle_sgd_round(double *X, const double *G, int64_t N, int64_t W, int64_t ld, int64_t ldg, double gamma,
+                     int32_t M, int32_t d, int64_t t, const uint8_t *alive)
+{
+    int rc = oracle_local_step(X, G, N, W, ld, ldg, gamma, alive);
+    if (rc != 0) return rc;
+    return oracle_round(X, N, W, ld, M, d, t, alive);
+}
+
 /* ---- several rounds ---------------------------------------------------- */
 
 /*

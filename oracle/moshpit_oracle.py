@@ -54,6 +54,8 @@ def _load():
         lib.oracle_dist_to_mean_subset.argtypes = [_ptr, _i64, _i64, _i64, _ptr]
         lib.oracle_dist_to_mean_subset.restype = _f64
         lib.oracle_schedule_masks.argtypes = [_i32, _f64, _u64, _i32, _i64, _i64, _i32, _ptr]
+        lib.oracle_local_step.argtypes = [_ptr, _ptr, _i64, _i64, _i64, _i64, _f64, _ptr]
+        lib.oracle_sgd_round.argtypes = [_ptr, _ptr, _i64, _i64, _i64, _i64, _f64, _i32, _i32, _i64, _ptr]
         lib.oracle_skip_filter.argtypes = [_i64, _i32, _i32, _i64, _ptr, _ptr]
         lib.oracle_random_permutation.argtypes = [_u64, _i64, _i64, _ptr]
         lib.oracle_grouped_round.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _i64, _i32, _ptr]
@@ -135,6 +137,26 @@ def schedule_masks(kind: int, p: float, seed: int, down: int, N: int, t0: int, r
     _check(_load().oracle_schedule_masks(kind, float(p), seed, down, N, t0, rounds,
                                          masks.ctypes.data), "schedule_masks")
     return masks
+
+
+def local_step(X: np.ndarray, G: np.ndarray, gamma: float, alive=None) -> None:
+    """theta_i <- theta_i - gamma * g_i for the peers that take part (Alg. 2, local iteration)."""
+    X, G = _state(X), _state(G)
+    N, W = X.shape
+    assert G.shape == X.shape
+    keep, ptr = _mask_ptr(alive, N)
+    _check(_load().oracle_local_step(X.ctypes.data, G.ctypes.data, N, W, X.strides[0] // 8, G.strides[0] // 8,
+                                     float(gamma), ptr), "local_step")
+
+
+def sgd_round(X: np.ndarray, G: np.ndarray, gamma: float, M: int, d: int, t: int, alive=None) -> None:
+    """theta_i <- group average of (theta_j - gamma * g_j) (Alg. 2, communication iteration)."""
+    X, G = _state(X), _state(G)
+    N, W = X.shape
+    assert G.shape == X.shape
+    keep, ptr = _mask_ptr(alive, N)
+    _check(_load().oracle_sgd_round(X.ctypes.data, G.ctypes.data, N, W, X.strides[0] // 8, G.strides[0] // 8,
+                                    float(gamma), M, d, t, ptr), "sgd_round")
 
 
 def skip_filter(N: int, M: int, d: int, t: int, alive) -> np.ndarray:

@@ -320,6 +320,59 @@ def test_dist_subset_is_numpy_definition():
 
 
 # --------------------------------------------------------------------------
+# Moshpit SGD step (Alg. 2)
+# --------------------------------------------------------------------------
+
+def test_sgd_round_matrix_form():
+    """X' = W (X - gamma * A G) with W the averaging matrix and A = diag(alive):
+    a wrong sign of gamma, a gradient applied to an absent peer or applied after
+    the averaging all change the result."""
+    rng = np.random.default_rng(31)
+    M, d, N = 3, 2, 9
+    X0, G = rng.normal(size=(N, 4)), rng.normal(size=(N, 4))
+    for trial in range(20):
+        alive = (rng.random(N) > 0.3).astype(np.uint8)
+        t, gamma = int(rng.integers(0, 4)), float(rng.uniform(0.01, 0.5))
+        W = averaging_matrix(N, M, d, t, alive)
+        want = W @ (X0 - gamma * alive[:, None] * G)
+        X = X0.copy()
+        orc.sgd_round(X, G, gamma, M, d, t, alive)
+        assert np.allclose(X, want, atol=1e-14, rtol=0)
+        Y = X0.copy()
+        orc.sgd_round(Y, G, 0.0, M, d, t, alive)
+        Z = X0.copy()
+        orc.round_(Z, M, d, t, alive)
+        assert np.array_equal(Y, Z)
+        L = X0.copy()
+        orc.local_step(L, G, gamma, alive)
+        assert np.allclose(L, X0 - gamma * alive[:, None] * G, atol=1e-15, rtol=0)
+
+
+def test_sgd_quadratic_closed_form():
+    """Alg. 2 on f_i(theta) = 1/2 ||theta - theta*||^2 with exact gradients and
+    all peers present: local steps and group averages both commute with the
+    mean over peers, so mean_K = theta* + (1 - gamma)^K (mean_0 - theta*), and
+    after a full sweep of d averaging iterations all peers agree."""
+    rng = np.random.default_rng(32)
+    M, d, N, P = 4, 2, 16, 5
+    X = rng.normal(size=(N, P)) * 3
+    star = rng.normal(size=P)
+    mean0 = X.mean(axis=0)
+    gamma, tau, t = 0.1, 3, 0
+    for k in range(12):
+        G = X - star
+        if (k + 1) % tau == 0:
+            orc.sgd_round(X, G, gamma, M, d, t)
+            t += 1
+        else:
+            orc.local_step(X, G, gamma)
+        want = star + (1 - gamma) ** (k + 1) * (mean0 - star)
+        assert np.allclose(X.mean(axis=0), want, atol=1e-13, rtol=0)
+    # four averaging iterations = two sweeps; peers drifted apart only by the (identical) local map
+    assert np.abs(X - X.mean(axis=0)).max() < 1e-13
+
+
+# --------------------------------------------------------------------------
 # group-skip failure behaviour (Sec. 3.1)
 # --------------------------------------------------------------------------
 
