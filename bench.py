@@ -195,6 +195,30 @@ def main() -> int:
                          "note": "includes the permutation kernel of every round"}
         log(f"[bench] random groups of {w.M}: {rg_ms:.3f} ms per round, {random_groups['gbps']} GB/s")
 
+    # Moshpit SGD communication iteration (Alg. 2): the round averages theta - gamma*g; every
+    # participating peer reads theta and g and writes theta: 3*s*P bytes
+    sgd = None
+    if not args.no_fused:
+        G = torch.empty_like(X)
+        G.normal_(0.0, 1.0)
+        stream = torch.cuda.current_stream(dev)
+        sg_masks = all_masks[: w.rounds]
+        for t in range(2):
+            m.sgd_round(t, G, 1e-3, sg_masks[t])
+        m.sync()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for t in range(w.rounds):
+            m.sgd_round(t, G, 1e-3, sg_masks[t])
+        e1.record(stream)
+        torch.cuda.synchronize()
+        sg_ms = e0.elapsed_time(e1) / w.rounds
+        sg_bytes = 3.0 * s * w.P * float(sg_masks.sum()) / w.rounds
+        sgd = {"ms_per_round": round(sg_ms, 4), "gbps": round(sg_bytes / (sg_ms * 1e-3) / 1e9, 1),
+               "note": "theta <- group mean of (theta - gamma*g); includes the host-to-device copy of each round's mask"}
+        log(f"[bench] Moshpit SGD round: {sg_ms:.3f} ms per round, {sgd['gbps']} GB/s")
+        del G
+
     copy_gbps = None
     if not args.no_copy_probe:
         nbytes = min(w.N * w.P * s, 8 * 2 ** 30)
@@ -268,6 +292,7 @@ def main() -> int:
                      "ms_per_launch": round(k1_ms_per_launch, 5)},
         "fused": fused,
         "random_groups": random_groups,
+        "sgd_round": sgd,
         "cpu_baseline": cpu,
     }
     m.close()

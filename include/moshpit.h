@@ -161,6 +161,22 @@ int moshpit_group_keys(moshpit_ctx *h, int64_t t, int32_t *keys_host);
 int moshpit_schedule_mask(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t rounds,
                           uint8_t *masks_host);
 
+/* Moshpit SGD (Alg. 2).  grad_dev: device, the stochastic gradients g_i as a
+ * matrix laid out like the state (same element type, P valid elements per row,
+ * rows grad_row_stride_elems apart), borrowed for the duration of the queued
+ * work.  alive_host as in moshpit_round: the peers of P_{k+1}.
+ * moshpit_local_step: an iteration without communication,
+ *   theta_i <- theta_i - gamma * g_i              for the peers that take part.
+ * moshpit_sgd_round: an iteration with one Moshpit All-Reduce round t fused in,
+ *   theta_i <- mean over i's round-t group of (theta_j - gamma * g_j);
+ * a peer that is alone in its group just takes its local step.  The product
+ * theta - gamma*g is formed in binary32 with one fused multiply-add; traffic is
+ * 3 * elem_size * P bytes per participating peer. */
+int moshpit_local_step(moshpit_ctx *h, const uint8_t *alive_host, const void *grad_dev,
+                       int64_t grad_row_stride_elems, float gamma);
+int moshpit_sgd_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host, const void *grad_dev,
+                      int64_t grad_row_stride_elems, float gamma);
+
 /* Averaging in random groups: the simplified scheme analysed in Thm 3.2 and
  * compared in Sec. 4.1.  Round t orders the peers by the key
  *   mix(mix(seed + 0xD1B54A32D192ED03*(t+1)) ^ i)       (mix as for the schedule)

@@ -23,7 +23,7 @@ RUN_DEFAULT, RUN_FUSED = 0, 1
 EXPORTS = [
     "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",
     "moshpit_run", "moshpit_dist_to_mean", "moshpit_dist_to_mean_subset", "moshpit_group_keys", "moshpit_schedule_mask",
-    "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
+    "moshpit_local_step", "moshpit_sgd_round", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
 ]
 
 
@@ -68,6 +68,8 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_dist_to_mean_subset.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.moshpit_group_keys.argtypes = [vp, i64, vp]
     lib.moshpit_schedule_mask.argtypes = [vp, ctypes.POINTER(_CSchedule), i64, i32, vp]
+    lib.moshpit_local_step.argtypes = [vp, vp, vp, i64, ctypes.c_float]
+    lib.moshpit_sgd_round.argtypes = [vp, i64, vp, vp, i64, ctypes.c_float]
     lib.moshpit_random_groups_round.argtypes = [vp, i64, ctypes.c_uint64, i32, vp]
     lib.moshpit_random_permutation.argtypes = [vp, i64, ctypes.c_uint64, vp]
     lib.moshpit_grouped_round.argtypes = [vp, vp, i64, i32, vp]
@@ -217,6 +219,22 @@ class Moshpit:
         if a.shape != (self.N,):
             raise ValueError("alive mask must have shape (N,)")
         return a, a.ctypes.data
+
+    def _grad(self, G):
+        X = self._state[0]
+        if G.dtype != X.dtype or tuple(G.shape) != (self.N, self.P) or G.stride(1) != 1 or not G.is_cuda:
+            raise ValueError("gradient tensor must match the state's dtype, shape and device")
+        return G.data_ptr(), G.stride(0)
+
+    def local_step(self, G, gamma: float, alive=None) -> None:
+        keep, ptr = self._alive_ptr(alive)
+        gp, gs = self._grad(G)
+        self._check(self._lib.moshpit_local_step(self._h, ptr, gp, gs, gamma), "local_step")
+
+    def sgd_round(self, t: int, G, gamma: float, alive=None) -> None:
+        keep, ptr = self._alive_ptr(alive)
+        gp, gs = self._grad(G)
+        self._check(self._lib.moshpit_sgd_round(self._h, t, ptr, gp, gs, gamma), "sgd_round")
 
     def random_groups_round(self, t: int, seed: int, group_size: int, alive=None) -> None:
         keep, ptr = self._alive_ptr(alive)

@@ -395,6 +395,60 @@ int queue_list_round(moshpit_ctx *h, const int32_t *index_dev, int64_t n_index, 
 }
 }  // namespace
 
+namespace {
+int check_grad(moshpit_ctx *h, const void *grad_dev, int64_t grad_row_stride)
+{
+    if (!grad_dev) return fail(h, MOSHPIT_EINVAL, "gradient pointer is NULL");
+    if (grad_row_stride < h->P) return fail(h, MOSHPIT_EINVAL, "gradient row stride < P");
+    const int64_t esize = h->dtype == MOSHPIT_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(grad_dev) % esize != 0)
+        return fail(h, MOSHPIT_EINVAL, "gradient pointer is not aligned to the element size");
+    return MOSHPIT_OK;
+}
+
+const uint8_t *stage_mask(moshpit_ctx *h, const uint8_t *alive_host, int *rc)
+{
+    *rc = MOSHPIT_OK;
+    if (!alive_host) return nullptr;
+    hipError_t e = hipMemcpyAsync(h->d_round_mask, alive_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice,
+                                  h->stream);
+    if (e != hipSuccess) *rc = fail(h, MOSHPIT_EHIP, "mask copy: %s", hipGetErrorString(e));
+    return h->d_round_mask;
+}
+}  // namespace
+
+int moshpit_sgd_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host, const void *grad_dev,
+                      int64_t grad_row_stride_elems, float gamma)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
+    rc = check_grad(h, grad_dev, grad_row_stride_elems);
+    if (rc != MOSHPIT_OK) return rc;
+    const uint8_t *alive_dev = stage_mask(h, alive_host, &rc);
+    if (rc != MOSHPIT_OK) return rc;
+    RoundGeom geom{h->N, h->M, axis_stride(h, t)};
+    geom.grad = static_cast<const char *>(grad_dev);
+    geom.grad_row_bytes = grad_row_stride_elems * (h->dtype == MOSHPIT_F32 ? 4 : 2);
+    geom.gamma = gamma;
+    HIP_TRY(h, launch_group_mean(h->X, h->dtype, h->P, h->row_stride, geom, alive_dev, h->tune, h->stream));
+    return MOSHPIT_OK;
+}
+
+int moshpit_local_step(moshpit_ctx *h, const uint8_t *alive_host, const void *grad_dev,
+                       int64_t grad_row_stride_elems, float gamma)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    rc = check_grad(h, grad_dev, grad_row_stride_elems);
+    if (rc != MOSHPIT_OK) return rc;
+    const uint8_t *alive_dev = stage_mask(h, alive_host, &rc);
+    if (rc != MOSHPIT_OK) return rc;
+    HIP_TRY(h, launch_local_step(h->X, h->dtype, h->N, h->P, h->row_stride, grad_dev, grad_row_stride_elems,
+                                 alive_dev, gamma, h->stream));
+    return MOSHPIT_OK;
+}
+
 int moshpit_random_permutation(moshpit_ctx *h, int64_t t, uint64_t seed, int32_t *perm_host)
 {
     if (!h) return MOSHPIT_EINVAL;

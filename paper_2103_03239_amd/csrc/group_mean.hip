@@ -114,11 +114,17 @@ template <bool NT, typename T> __device__ __forceinline__ void store_vec(T *p, c
 // work_items   groups * tiles
 // IDX          groups are consecutive chunks of M entries of the peer list
 //              index[0..n_index) (e.g. a random permutation) instead of grid lines
-template <int DT, int VE, int COLS, int U, bool NT, bool IDX>
+// SGD          the Moshpit SGD communication step (Alg. 2): what is averaged is
+//              theta_j - gamma * g_j, g read from the matrix G laid out like X
+//              (rows g_row_bytes apart); a peer that is alone in its group still
+//              takes its local step
+template <int DT, int VE, int COLS, int U, bool NT, bool IDX, bool SGD>
 __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t row_bytes, int64_t nvec,
                                                             const uint8_t *__restrict__ alive, int32_t M,
                                                             int64_t S, int64_t tiles, int64_t work_items,
-                                                            const int32_t *__restrict__ index, int64_t n_index)
+                                                            const int32_t *__restrict__ index, int64_t n_index,
+                                                            const char *__restrict__ G, int64_t g_row_bytes,
+                                                            float gamma)
 {
     typedef Vec<DT, VE> V;
     typedef typename V::mem_t mem_t;
@@ -142,7 +148,7 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
         }
         const uint64_t live = __ballot(takes_part);
         const int cnt = __popcll(live);
-        if (cnt < 2) continue;                       // nothing to average: rows stay as they are
+        if (cnt < (SGD ? 1 : 2)) continue;           // nothing to do: rows stay as they are
 
         const int64_t v0 = tile * (static_cast<int64_t>(kBlock) * COLS) + threadIdx.x;
         bool in_row[COLS];
@@ -173,22 +179,41 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
             const uint64_t bits = (live >> j0) & (U >= 64 ? ~0ull : ((1ull << (U % 64)) - 1ull));
             if (bits == 0) continue;
             mem_t buf[U][COLS];
+            mem_t gbuf[SGD ? U : 1][COLS];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int c = 0; c < COLS; ++c) buf[u][c] = V::zero();
+                for (int c = 0; c < COLS; ++c) {
+                    buf[u][c] = V::zero();
+                    if constexpr (SGD) gbuf[u][c] = V::zero();
+                }
                 if ((bits >> u) & 1ull) {
                     const mem_t *src = reinterpret_cast<const mem_t *>(row_ptr(j0 + u));
 #pragma unroll
                     for (int c = 0; c < COLS; ++c)
                         if (in_row[c]) buf[u][c] = load_vec<NT>(src + c * kBlock);
+                    if constexpr (SGD) {
+                        const mem_t *gsrc = reinterpret_cast<const mem_t *>(
+                            G + (base + (j0 + u) * S) * g_row_bytes + v0 * static_cast<int64_t>(sizeof(mem_t)));
+#pragma unroll
+                        for (int c = 0; c < COLS; ++c)
+                            if (in_row[c]) gbuf[u][c] = load_vec<NT>(gsrc + c * kBlock);
+                    }
                 }
             }
 #pragma unroll
             for (int c = 0; c < COLS; ++c) {
                 float f[U][NE];
 #pragma unroll
-                for (int u = 0; u < U; ++u) V::widen(buf[u][c], f[u]);
+                for (int u = 0; u < U; ++u) {
+                    V::widen(buf[u][c], f[u]);
+                    if constexpr (SGD) {
+                        float gf[NE];
+                        V::widen(gbuf[u][c], gf);
+#pragma unroll
+                        for (int e = 0; e < NE; ++e) f[u][e] = fmaf(-gamma, gf[e], f[u][e]);
+                    }
+                }
 #pragma unroll
                 for (int s = 1; s < U; s *= 2)
 #pragma unroll
@@ -224,7 +249,7 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
 // The kernel uses no LDS.  The dynamic-LDS size of the launch is only a
 // throttle: a block that reserves lds bytes lets floor(160 KiB / lds) blocks
 // share a compute unit, which bounds the number of row loads in flight.
-template <int DT, int VE, int COLS, int U, bool NT, bool IDX = false>
+template <int DT, int VE, int COLS, int U, bool NT, bool IDX = false, bool SGD = false>
 hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *alive, const RoundGeom &geom,
                       int block, int waves_per_cu, hipStream_t stream)
 {
@@ -235,7 +260,7 @@ hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *a
     const int64_t work = groups * tiles;
     if (work <= 0) return hipSuccess;
     const int64_t grid = work < 0x7fffffffLL ? work : 0x7fffffffLL;
-    auto kernel = group_mean_kernel<DT, VE, COLS, U, NT, IDX>;
+    auto kernel = group_mean_kernel<DT, VE, COLS, U, NT, IDX, SGD>;
     size_t lds = 0;
     if (waves_per_cu > 0 && waves_per_cu < 32) {
         int blocks_per_cu = waves_per_cu / (block / 64);
@@ -251,7 +276,8 @@ hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *a
     }
     kernel<<<dim3(static_cast<uint32_t>(grid)), dim3(block), lds, stream>>>(X, row_bytes, nvec, alive, geom.M,
                                                                             geom.S, tiles, work, geom.index,
-                                                                            geom.n_index);
+                                                                            geom.n_index, geom.grad, geom.grad_row_bytes,
+                                                                            geom.gamma);
     return hipGetLastError();
 }
 
@@ -265,6 +291,14 @@ hipError_t launch_shape(int cols, int unroll, bool nt, char *X, int64_t row_byte
         if (cols == 2 && unroll == 8) return launch_one<DT, VE, 2, 8, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
         if (cols == 4 && unroll == 4) return launch_one<DT, VE, 4, 4, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
         if (cols == 4 && unroll == 2) return launch_one<DT, VE, 4, 2, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        return hipErrorInvalidValue;
+    }
+    if (geom.grad != nullptr) {
+        // Moshpit SGD step: the default shapes only, streaming accesses
+        if (cols == 1 && unroll == 16) return launch_one<DT, VE, 1, 16, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        if (cols == 2 && unroll == 8) return launch_one<DT, VE, 2, 8, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        if (cols == 4 && unroll == 4) return launch_one<DT, VE, 4, 4, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        if (cols == 4 && unroll == 2) return launch_one<DT, VE, 4, 2, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
         return hipErrorInvalidValue;
     }
 #define MOSHPIT_CASE(C, UU)                                                                          \
@@ -293,7 +327,9 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
 {
     const int64_t esize = dtype == 0 ? 4 : 2;
     const int64_t row_bytes = row_stride * esize;
-    const bool aligned = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (row_bytes % 16 == 0);
+    const bool aligned = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (row_bytes % 16 == 0) &&
+                         (geom.grad == nullptr || (reinterpret_cast<uintptr_t>(geom.grad) % 16 == 0 &&
+                                                   geom.grad_row_bytes % 16 == 0));
     const int64_t ve = dtype == 0 ? 4 : 8;
     const int64_t nvec = aligned ? P / ve : 0;          // 128-bit part of every row
     const int64_t tail0 = nvec * ve;                    // first column of the element-wise part
@@ -304,7 +340,7 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     // about 20-24 MiB in flight on the chip.  More than that and the HBM
     // controllers see too many open pages; less and latency is not covered.
     int cols = tune.cols, unroll = tune.unroll;
-    if (cols <= 0 || unroll <= 0 || geom.index != nullptr) {
+    if (cols <= 0 || unroll <= 0 || geom.index != nullptr || geom.grad != nullptr) {
         if (geom.M > 8) { unroll = 16; cols = 1; }
         else if (geom.M > 4) { unroll = 8; cols = 2; }
         else if (geom.M > 2) { unroll = 4; cols = 4; }
@@ -315,7 +351,7 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     int wpc = tune.waves_per_cu;
     if (wpc <= 0) {
         const int rows = geom.M < unroll ? geom.M : unroll;
-        const int kib_per_wave = rows * cols * (block / 64);
+        const int kib_per_wave = rows * cols * (block / 64) * (geom.grad != nullptr ? 2 : 1);
         wpc = (dtype == 0 ? 80 : 96) / kib_per_wave * (block / 64);
         if (wpc < 4) wpc = 4;
         if (wpc > 32) wpc = 32;
@@ -330,7 +366,12 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     }
     if (tail0 < P) {
         char *tbase = base + tail0 * esize;
-        if (geom.index != nullptr)
+        if (geom.grad != nullptr) {
+            RoundGeom tg = geom;
+            tg.grad = geom.grad + tail0 * esize;
+            e = dtype == 0 ? launch_one<0, 1, 1, 8, false, false, true>(tbase, row_bytes, P - tail0, alive, tg, 256, 32, stream)
+                           : launch_one<1, 1, 1, 8, false, false, true>(tbase, row_bytes, P - tail0, alive, tg, 256, 32, stream);
+        } else if (geom.index != nullptr)
             e = dtype == 0 ? launch_one<0, 1, 1, 8, false, true>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream)
                            : launch_one<1, 1, 1, 8, false, true>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream);
         else
@@ -338,6 +379,67 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
                            : launch_one<1, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream);
     }
     return e;
+}
+
+// ---- local iteration of Moshpit SGD (Alg. 2): theta_i <- theta_i - gamma * g_i ----
+
+namespace {
+template <int DT, int VE>
+__global__ __launch_bounds__(256) void local_step_kernel(char *X, int64_t row_bytes, const char *__restrict__ G,
+                                                         int64_t g_row_bytes, int64_t nvec,
+                                                         const uint8_t *__restrict__ alive, float gamma, int64_t tiles)
+{
+    typedef Vec<DT, VE> V;
+    typedef typename V::mem_t mem_t;
+    constexpr int NE = V::NE;
+    const int64_t row = blockIdx.x / tiles;
+    const int64_t tile = blockIdx.x - row * tiles;
+    if (alive != nullptr && alive[row] == 0) return;
+    const int64_t v = tile * 256 + threadIdx.x;
+    if (v >= nvec) return;
+    mem_t *x = reinterpret_cast<mem_t *>(X + row * row_bytes) + v;
+    const mem_t *g = reinterpret_cast<const mem_t *>(G + row * g_row_bytes) + v;
+    float xf[NE], gf[NE];
+    V::widen(load_vec<true>(x), xf);
+    V::widen(load_vec<true>(g), gf);
+#pragma unroll
+    for (int e = 0; e < NE; ++e) xf[e] = fmaf(-gamma, gf[e], xf[e]);
+    store_vec<true>(x, V::narrow(xf));
+}
+
+template <int DT, int VE>
+hipError_t launch_local(char *X, int64_t row_bytes, const char *G, int64_t g_row_bytes, int64_t nvec, int64_t N,
+                        const uint8_t *alive, float gamma, hipStream_t stream)
+{
+    if (nvec <= 0) return hipSuccess;
+    const int64_t tiles = (nvec + 255) / 256;
+    const int64_t blocks = tiles * N;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    local_step_kernel<DT, VE><<<dim3(static_cast<uint32_t>(blocks)), dim3(256), 0, stream>>>(X, row_bytes, G, g_row_bytes,
+                                                                                              nvec, alive, gamma, tiles);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_local_step(void *X, int dtype, int64_t N, int64_t P, int64_t row_stride, const void *G,
+                             int64_t g_row_stride, const uint8_t *alive, float gamma, hipStream_t stream)
+{
+    const int64_t esize = dtype == 0 ? 4 : 2;
+    const int64_t row_bytes = row_stride * esize, g_row_bytes = g_row_stride * esize;
+    const bool aligned = reinterpret_cast<uintptr_t>(X) % 16 == 0 && row_bytes % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(G) % 16 == 0 && g_row_bytes % 16 == 0;
+    const int64_t ve = dtype == 0 ? 4 : 8;
+    const int64_t nvec = aligned ? P / ve : 0;
+    const int64_t tail0 = nvec * ve;
+    char *x = static_cast<char *>(X);
+    const char *g = static_cast<const char *>(G);
+    hipError_t e = dtype == 0 ? launch_local<0, 4>(x, row_bytes, g, g_row_bytes, nvec, N, alive, gamma, stream)
+                              : launch_local<1, 8>(x, row_bytes, g, g_row_bytes, nvec, N, alive, gamma, stream);
+    if (e != hipSuccess || tail0 >= P) return e;
+    return dtype == 0 ? launch_local<0, 1>(x + tail0 * esize, row_bytes, g + tail0 * esize, g_row_bytes, P - tail0, N,
+                                           alive, gamma, stream)
+                      : launch_local<1, 1>(x + tail0 * esize, row_bytes, g + tail0 * esize, g_row_bytes, P - tail0, N,
+                                           alive, gamma, stream);
 }
 
 // ---- plain copy, the streaming ceiling the round kernel is measured against ----

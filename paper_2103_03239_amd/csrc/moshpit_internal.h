@@ -30,6 +30,10 @@ struct RoundGeom {
     int64_t S;
     const int32_t *index = nullptr;
     int64_t n_index = 0;
+    // Moshpit SGD step: average theta - gamma * g, g from `grad` (device, laid out like X)
+    const char *grad = nullptr;
+    int64_t grad_row_bytes = 0;
+    float gamma = 0.f;
 };
 
 // Queue one averaging round on `stream`.  X: device, row-major, `P` valid
@@ -37,6 +41,10 @@ struct RoundGeom {
 // (non-zero = takes part) or nullptr (all take part).
 hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, const RoundGeom &geom,
                              const uint8_t *alive, const MeanTuning &tune, hipStream_t stream);
+
+// Queue the local iteration of Moshpit SGD: X[i] -= gamma * G[i] for the rows that take part.
+hipError_t launch_local_step(void *X, int dtype, int64_t N, int64_t P, int64_t row_stride, const void *G,
+                             int64_t g_row_stride, const uint8_t *alive, float gamma, hipStream_t stream);
 
 // Number of partial sums launch_dist_partials writes for this shape.
 int64_t dist_partials_count(int dtype, int64_t P, int64_t row_stride, const void *X);

@@ -463,3 +463,64 @@ def test_group_skip_schedule(M, d, P, dtype, p, fused):
         sched2 = binding.Schedule(kind=binding.SCHED_EXPLICIT, explicit_masks=raw, group_skip=True)
         assert np.array_equal(m.schedule_mask(sched2, 0, rounds), eff)
     assert_state_close(to_f64(X), ref, TOL[dtype], "group skip")
+
+
+# --------------------------------------------------------------------------
+# Moshpit SGD iterations (Alg. 2)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,d,P,dtype,p,pad", [(16, 2, 3_000, 0, 0.1, 0), (4, 3, 1_001, 0, 0.2, 3), (32, 2, 520, 1, 0.1, 0),
+                                                (3, 2, 77, 1, 0.3, 1), (8, 2, 4_096, 0, 0.0, 0)])
+def test_sgd_iterations(M, d, P, dtype, p, pad):
+    """tau = 2: a local step, then a step with the averaging round fused in."""
+    N, iters, gamma = M ** d, 6, 0.05
+    w = inputs.Workload("sgd", N, M, d, P, dtype, "peer_offset", 1, p, 0, iters, 61, 62)
+    say(f"sgd {w}")
+    X = inputs.make_state(w, DEV, row_stride=P + pad)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(63)
+    ref = to_f64(X).copy()
+    masks = orc.schedule_masks(1, p, 62, 0, N, 0, iters)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(X)
+        t = 0
+        for k in range(iters):
+            G = torch.randn(N, P + pad, generator=gen, device=DEV).to(w.torch_dtype)[:, :P]
+            Gref = to_f64(G).copy()
+            alive = masks[k] if p > 0 else None
+            if k % 2 == 1:
+                m.sgd_round(t, G, gamma, alive)
+                orc.sgd_round(ref, Gref, np.float32(gamma), M, d, t, alive)
+                t += 1
+            else:
+                m.local_step(G, gamma, alive)
+                orc.local_step(ref, Gref, np.float32(gamma), alive)
+            m.sync()
+        assert_state_close(to_f64(X), ref, TOL[dtype], w.name)
+
+
+def test_sgd_quadratic_mean_trajectory():
+    """Exact gradients of 1/2 ||theta - theta*||^2, all peers present: the mean
+    over peers follows theta* + (1-gamma)^K (mean_0 - theta*) whatever the
+    averaging does (closed form pinned for the oracle on the CPU)."""
+    M, d, P, gamma = 8, 2, 2_048, 0.1
+    N = M * M
+    w = inputs.Workload("sgd-quad", N, M, d, P, 0, "peer_offset", 0, 0.0, 0, 1, 71, 72)
+    X = inputs.make_state(w, DEV)
+    star = torch.linspace(-1, 1, P, device=DEV)
+    mean0 = X.double().mean(dim=0)
+    with binding.Moshpit(N, P, M, d, 0) as m:
+        m.bind_state(X)
+        t = 0
+        for k in range(8):
+            G = X - star
+            if k % 2 == 1:
+                m.sgd_round(t, G, gamma)
+                t += 1
+            else:
+                m.local_step(G, gamma)
+            m.sync()
+    want = star.double() + (1 - np.float64(np.float32(gamma))) ** 8 * (mean0 - star.double())
+    got = X.double().mean(dim=0)
+    assert float((got - want).abs().max()) <= 2e-6 * float(want.abs().max())
+    assert float((X - X.mean(dim=0)).abs().max()) <= 1e-5
