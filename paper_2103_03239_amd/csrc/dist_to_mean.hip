@@ -10,8 +10,8 @@
 // grid) the same runs over the rows that hold a peer, shifted by the first one.
 //
 // Mapping.  A block owns a tile of 64 vectors (one 128-bit vector per lane,
-// 1 KiB per row); its W waves take rows w, w+W, ... with 8 row loads in flight
-// each, then combine their per-column sums through LDS, reduce across lanes
+// 1 KiB per row); its W waves (W chosen so that a wave sees about 256 rows) take
+// rows w, w+W, ... with 8 non-temporal row loads in flight each, then combine their per-column sums through LDS, reduce across lanes
 // and write ONE partial per block.  A second one-block kernel adds the partials
 // in a fixed order, so the result does not depend on scheduling.
 #include "moshpit_internal.h"
@@ -22,7 +22,7 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 8;          // waves per block
+constexpr int kMaxWaves = 16;      // waves per block: 1, 2, 4, 8 or 16
 constexpr int kRowsInFlight = 8;   // row loads issued before the first use
 
 template <int DT, int VE> struct Wide;
@@ -68,7 +68,7 @@ template <> struct Wide<1, 1> {
 // present   nullptr, or N bytes: rows with 0 are left out of mean and sum
 //           (vertices of a partly filled grid that hold no peer)
 // first     index of the first row that counts; n = number of rows that count
-template <int DT, int VE>
+template <int DT, int VE, int kWaves>
 __global__ __launch_bounds__(kWaves * 64) void dist_partial_kernel(const char *__restrict__ X, int64_t row_bytes,
                                                                     int64_t nvec, int64_t N,
                                                                     double *__restrict__ partials,
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kWaves * 64) void dist_partial_kernel(const char *_
         for (int u = 0; u < kRowsInFlight; ++u) {
             const int64_t i = i0 + static_cast<int64_t>(u) * kWaves;
             have[u] = valid && i < N && (present == nullptr || present[i] != 0);
-            if (have[u]) buf[u] = *reinterpret_cast<const mem_t *>(col + i * row_bytes);
+            if (have[u]) buf[u] = __builtin_nontemporal_load(reinterpret_cast<const mem_t *>(col + i * row_bytes));
         }
 #pragma unroll
         for (int u = 0; u < kRowsInFlight; ++u) {
@@ -188,24 +188,36 @@ hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, i
     const int64_t esize = dtype == 0 ? 4 : 2;
     const int64_t row_bytes = row_stride * esize;
     const char *base = static_cast<const char *>(X);
-    const dim3 block(kWaves * 64);
-    if (s.blocks_vec > 0) {
-        const dim3 grid(static_cast<uint32_t>(s.blocks_vec));
-        if (dtype == 0)
-            dist_partial_kernel<0, 4><<<grid, block, 0, stream>>>(base, row_bytes, s.nvec, N, partials, present, first, n);
-        else
-            dist_partial_kernel<1, 8><<<grid, block, 0, stream>>>(base, row_bytes, s.nvec, N, partials, present, first, n);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+    // about 256 rows per wave (measured best on MI355X for 64 <= N <= 4096)
+    int waves = 1;
+    while (waves < kMaxWaves && N / (waves * 2) >= 256) waves *= 2;
+    const char *tbase = base + s.tail0 * esize;
+    double *tpart = partials + s.blocks_vec;
+#define MOSHPIT_DIST(W)                                                                                        \
+    if (waves == W) {                                                                                          \
+        const dim3 block(W * 64);                                                                              \
+        if (s.blocks_vec > 0) {                                                                                \
+            const dim3 grid(static_cast<uint32_t>(s.blocks_vec));                                              \
+            if (dtype == 0)                                                                                    \
+                dist_partial_kernel<0, 4, W><<<grid, block, 0, stream>>>(base, row_bytes, s.nvec, N, partials, present, first, n); \
+            else                                                                                               \
+                dist_partial_kernel<1, 8, W><<<grid, block, 0, stream>>>(base, row_bytes, s.nvec, N, partials, present, first, n); \
+        }                                                                                                      \
+        if (s.blocks_tail > 0) {                                                                               \
+            const dim3 grid(static_cast<uint32_t>(s.blocks_tail));                                             \
+            if (dtype == 0)                                                                                    \
+                dist_partial_kernel<0, 1, W><<<grid, block, 0, stream>>>(tbase, row_bytes, P - s.tail0, N, tpart, present, first, n); \
+            else                                                                                               \
+                dist_partial_kernel<1, 1, W><<<grid, block, 0, stream>>>(tbase, row_bytes, P - s.tail0, N, tpart, present, first, n); \
+        }                                                                                                      \
     }
-    if (s.blocks_tail > 0) {
-        const dim3 grid(static_cast<uint32_t>(s.blocks_tail));
-        const char *tbase = base + s.tail0 * esize;
-        double *tpart = partials + s.blocks_vec;
-        if (dtype == 0)
-            dist_partial_kernel<0, 1><<<grid, block, 0, stream>>>(tbase, row_bytes, P - s.tail0, N, tpart, present, first, n);
-        else
-            dist_partial_kernel<1, 1><<<grid, block, 0, stream>>>(tbase, row_bytes, P - s.tail0, N, tpart, present, first, n);
+    MOSHPIT_DIST(1)
+    MOSHPIT_DIST(2)
+    MOSHPIT_DIST(4)
+    MOSHPIT_DIST(8)
+    MOSHPIT_DIST(16)
+#undef MOSHPIT_DIST
+    {
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
