@@ -524,3 +524,32 @@ def test_sgd_quadratic_mean_trajectory():
     got = X.double().mean(dim=0)
     assert float((got - want).abs().max()) <= 2e-6 * float(want.abs().max())
     assert float((X - X.mean(dim=0)).abs().max()) <= 1e-5
+
+
+# --------------------------------------------------------------------------
+# streams and several handles
+# --------------------------------------------------------------------------
+
+def test_user_stream_and_two_handles():
+    """Work is queued on the stream given to bind_state; two handles on two
+    streams do not disturb each other."""
+    M, d, P, rounds = 8, 2, 50_000, 6
+    N = M ** d
+    wa = inputs.Workload("stream-a", N, M, d, P, 0, "normal", 1, 0.1, 0, rounds, 81, 82)
+    wb = inputs.Workload("stream-b", N, M, d, P, 1, "peer_offset", 2, 0.2, 2, rounds, 83, 84)
+    A, B = inputs.make_state(wa, DEV), inputs.make_state(wb, DEV)
+    ref_a, ref_b = to_f64(A).copy(), to_f64(B).copy()
+    orc.run(ref_a, M, d, 0, rounds, orc.schedule_masks(1, 0.1, 82, 0, N, 0, rounds))
+    orc.run(ref_b, M, d, 0, rounds, orc.schedule_masks(2, 0.2, 84, 2, N, 0, rounds))
+    sa, sb = torch.cuda.Stream(device=DEV), torch.cuda.Stream(device=DEV)
+    torch.cuda.synchronize()
+    with binding.Moshpit(N, P, M, d, 0) as ma, binding.Moshpit(N, P, M, d, 1) as mb:
+        ma.bind_state(A, sa)
+        mb.bind_state(B, sb)
+        for r in range(rounds):                       # interleave the two handles round by round
+            ma.run(r, 1, sched_of(wa))
+            mb.run(r, 1, sched_of(wb), flags=binding.RUN_FUSED)
+        ma.sync()
+        mb.sync()
+    assert_state_close(to_f64(A), ref_a, TOL[0], "stream a")
+    assert_state_close(to_f64(B), ref_b, TOL[1], "stream b")
