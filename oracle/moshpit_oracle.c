@@ -391,6 +391,97 @@ int oracle_random_groups_round(double *X, int64_t N, int64_t W, int64_t ld, uint
     return rc;
 }
 
+/* ---- Alg. 1 with chunk-index keys ---------------------------------------- */
+
+/*
+ * Alg. 1 as written: every peer carries the key C_i of its d-1 most recent
+ * chunk indices (Eq. 1); peers with equal keys form a group; after the group's
+ * all-reduce each member receives a chunk index c_i that is unique within the
+ * group (its position in the randomly ordered list peers_t) and shifts it into
+ * its key: C_i := (C_i[1:], c_i).  Two peers that just averaged together
+ * therefore never share the next group (Sec. 3.1).
+ *
+ * Readings where the paper is silent:
+ *   - initial key (Eq. 2): coordinates 1..d-1 of the peer index, so the first
+ *     round groups M consecutive peers, like the static grid;
+ *   - the random order of peers_t: ascending order_key(seed, t, i), ties by
+ *     index; c_i = rank among the members that take part;
+ *   - a peer that does not take part keeps vector and key;
+ *   - if more than M peers that take part share a key (possible once peers
+ *     with stale keys return), the ordered list is cut into consecutive groups
+ *     of M; c_i is the position within its group of at most M.
+ * keys: N x (d-1) int32, row-major, updated in place (d == 1: no key, all
+ * peers share the empty key).
+ */
+int oracle_dynamic_init(int64_t N, int32_t M, int32_t d, int32_t *keys)
+{
+    if (d < 1 || d > ORACLE_MAX_D || M < 1) return -1;
+    for (int64_t i = 0; i < N; ++i) {
+        int32_t c[ORACLE_MAX_D];
+        oracle_digits(i, M, d, c);
+        for (int32_t q = 1; q < d; ++q) keys[i * (d - 1) + (q - 1)] = c[q];
+    }
+    return 0;
+}
+
+int oracle_dynamic_round(double *X, int64_t N, int64_t W, int64_t ld, int32_t M, int32_t d, int32_t *keys,
+                         uint64_t seed, int64_t t, const uint8_t *alive)
+{
+    if (d < 1 || d > ORACLE_MAX_D || M < 1 || t < 0) return -1;
+    const int32_t kd = d - 1;
+    uint8_t *done = (uint8_t *)calloc((size_t)(N > 0 ? N : 1), 1);
+    int64_t *members = (int64_t *)malloc(sizeof(int64_t) * (size_t)(N > 0 ? N : 1));
+    int32_t *chunk = (int32_t *)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+    double *mean = (double *)malloc(sizeof(double) * (size_t)(W > 0 ? W : 1));
+    if (!done || !members || !chunk || !mean) { free(done); free(members); free(chunk); free(mean); return -2; }
+
+    for (int64_t lead = 0; lead < N; ++lead) {
+        if (done[lead] || (alive != NULL && alive[lead] == 0)) continue;
+        /* everybody who takes part and carries lead's key */
+        int64_t k = 0;
+        for (int64_t j = lead; j < N; ++j) {
+            if (done[j] || (alive != NULL && alive[j] == 0)) continue;
+            int same = 1;
+            for (int32_t q = 0; q < kd; ++q)
+                if (keys[j * kd + q] != keys[lead * kd + q]) same = 0;
+            if (same) { members[k++] = j; done[j] = 1; }
+        }
+        /* the random order of peers_t: insertion sort by (order_key, index) */
+        for (int64_t a = 1; a < k; ++a) {
+            int64_t m = members[a];
+            uint64_t km = order_key(seed, t, m);
+            int64_t b = a - 1;
+            while (b >= 0) {
+                uint64_t kb = order_key(seed, t, members[b]);
+                if (kb < km || (kb == km && members[b] < m)) break;
+                members[b + 1] = members[b];
+                --b;
+            }
+            members[b + 1] = m;
+        }
+        /* consecutive groups of at most M: average, hand out chunk indices */
+        for (int64_t g0 = 0; g0 < k; g0 += M) {
+            int64_t g1 = g0 + M < k ? g0 + M : k;
+            for (int64_t c = 0; c < W; ++c) mean[c] = 0.0;
+            for (int64_t a = g0; a < g1; ++a)
+                for (int64_t c = 0; c < W; ++c) mean[c] += X[members[a] * ld + c];
+            for (int64_t c = 0; c < W; ++c) mean[c] = mean[c] / (double)(g1 - g0);
+            for (int64_t a = g0; a < g1; ++a) {
+                for (int64_t c = 0; c < W; ++c) X[members[a] * ld + c] = mean[c];
+                chunk[members[a]] = (int32_t)(a - g0);
+            }
+        }
+    }
+    /* C_i := (C_i[1:], c_i) for the peers that took part */
+    for (int64_t i = 0; i < N; ++i) {
+        if (!done[i] || kd == 0) continue;
+        for (int32_t q = 0; q + 1 < kd; ++q) keys[i * kd + q] = keys[i * kd + q + 1];
+        keys[i * kd + kd - 1] = chunk[i];
+    }
+    free(done); free(members); free(chunk); free(mean);
+    return 0;
+}
+
 /* ---- Moshpit SGD step (Alg. 2) ------------------------------------------ */
 
 /*

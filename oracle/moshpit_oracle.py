@@ -54,6 +54,8 @@ def _load():
         lib.oracle_dist_to_mean_subset.argtypes = [_ptr, _i64, _i64, _i64, _ptr]
         lib.oracle_dist_to_mean_subset.restype = _f64
         lib.oracle_schedule_masks.argtypes = [_i32, _f64, _u64, _i32, _i64, _i64, _i32, _ptr]
+        lib.oracle_dynamic_init.argtypes = [_i64, _i32, _i32, _ptr]
+        lib.oracle_dynamic_round.argtypes = [_ptr, _i64, _i64, _i64, _i32, _i32, _ptr, _u64, _i64, _ptr]
         lib.oracle_local_step.argtypes = [_ptr, _ptr, _i64, _i64, _i64, _i64, _f64, _ptr]
         lib.oracle_sgd_round.argtypes = [_ptr, _ptr, _i64, _i64, _i64, _i64, _f64, _i32, _i32, _i64, _ptr]
         lib.oracle_skip_filter.argtypes = [_i64, _i32, _i32, _i64, _ptr, _ptr]
@@ -137,6 +139,23 @@ def schedule_masks(kind: int, p: float, seed: int, down: int, N: int, t0: int, r
     _check(_load().oracle_schedule_masks(kind, float(p), seed, down, N, t0, rounds,
                                          masks.ctypes.data), "schedule_masks")
     return masks
+
+
+def dynamic_init(N: int, M: int, d: int) -> np.ndarray:
+    """Initial chunk-index keys (Eq. 2): int32 [N, d-1]."""
+    keys = np.zeros((N, max(d - 1, 0)), dtype=np.int32)
+    _check(_load().oracle_dynamic_init(N, M, d, keys.ctypes.data), "dynamic_init")
+    return keys
+
+
+def dynamic_round(X: np.ndarray, M: int, d: int, keys: np.ndarray, seed: int, t: int, alive=None) -> None:
+    """One round of Alg. 1 with chunk-index keys; X and keys are updated in place."""
+    X = _state(X)
+    N, W = X.shape
+    assert keys.dtype == np.int32 and keys.shape == (N, max(d - 1, 0)) and keys.flags.c_contiguous
+    keep, ptr = _mask_ptr(alive, N)
+    _check(_load().oracle_dynamic_round(X.ctypes.data, N, W, X.strides[0] // 8, M, d, keys.ctypes.data, seed, t, ptr),
+           "dynamic_round")
 
 
 def local_step(X: np.ndarray, G: np.ndarray, gamma: float, alive=None) -> None:
