@@ -195,6 +195,28 @@ def main() -> int:
                          "note": "includes the permutation kernel of every round"}
         log(f"[bench] random groups of {w.M}: {rg_ms:.3f} ms per round, {random_groups['gbps']} GB/s")
 
+    # Alg. 1 with chunk-index keys: integer grouping kernels + the peer-list instantiation of the
+    # group-mean kernel; bytes counted as 2*s*P per participating peer
+    dynamic = None
+    if not args.no_fused and w.N <= 65536:
+        stream = torch.cuda.current_stream(dev)
+        dy_masks = all_masks[: w.rounds]
+        m.dynamic_reset()
+        for t in range(2):
+            m.dynamic_round(t, 55, dy_masks[t])
+        m.sync()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for t in range(w.rounds):
+            m.dynamic_round(2 + t, 55, dy_masks[t])
+        e1.record(stream)
+        torch.cuda.synchronize()
+        dy_ms = e0.elapsed_time(e1) / w.rounds
+        dy_bytes = 2.0 * s * w.P * float(dy_masks.sum()) / w.rounds
+        dynamic = {"ms_per_round": round(dy_ms, 4), "gbps": round(dy_bytes / (dy_ms * 1e-3) / 1e9, 1),
+                   "note": "includes the key/grouping kernels and the host-to-device copy of each round's mask"}
+        log(f"[bench] chunk-index-key round: {dy_ms:.3f} ms per round, {dynamic['gbps']} GB/s")
+
     # Moshpit SGD communication iteration (Alg. 2): the round averages theta - gamma*g; every
     # participating peer reads theta and g and writes theta: 3*s*P bytes
     sgd = None
@@ -292,6 +314,7 @@ def main() -> int:
                      "ms_per_launch": round(k1_ms_per_launch, 5)},
         "fused": fused,
         "random_groups": random_groups,
+        "dynamic_keys": dynamic,
         "sgd_round": sgd,
         "cpu_baseline": cpu,
     }

@@ -161,6 +161,22 @@ int moshpit_group_keys(moshpit_ctx *h, int64_t t, int32_t *keys_host);
 int moshpit_schedule_mask(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t rounds,
                           uint8_t *masks_host);
 
+/* Alg. 1 with chunk-index keys (Eq. 1 and the key shift of Alg. 1) instead of
+ * fixed grid coordinates.  The handle keeps a key of d-1 chunk indices per
+ * peer, initially coordinates 1..d-1 of the peer index (Eq. 2).  Round t:
+ * the peers that take part and carry equal keys are ordered by
+ *   mix(mix(seed + 0xD1B54A32D192ED03*(t+1)) ^ i), ties by index
+ * (the random order of peers_t), cut into consecutive groups of at most M,
+ * averaged group by group, and every member shifts its position in its group
+ * into its key: C_i := (C_i[1:], c_i).  A peer that sits the round out keeps
+ * vector and key.  With all peers present, d rounds give the exact global mean
+ * whatever the seed.  N <= 65536.
+ * moshpit_dynamic_reset restores the initial keys; moshpit_dynamic_keys copies
+ * the keys to the host (N x (d-1) int32, row-major; waits). */
+int moshpit_dynamic_reset(moshpit_ctx *h);
+int moshpit_dynamic_round(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *alive_host);
+int moshpit_dynamic_keys(moshpit_ctx *h, int32_t *keys_host);
+
 /* Moshpit SGD (Alg. 2).  grad_dev: device, the stochastic gradients g_i as a
  * matrix laid out like the state (same element type, P valid elements per row,
  * rows grad_row_stride_elems apart), borrowed for the duration of the queued

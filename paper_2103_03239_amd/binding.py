@@ -23,7 +23,7 @@ RUN_DEFAULT, RUN_FUSED = 0, 1
 EXPORTS = [
     "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",
     "moshpit_run", "moshpit_dist_to_mean", "moshpit_dist_to_mean_subset", "moshpit_group_keys", "moshpit_schedule_mask",
-    "moshpit_local_step", "moshpit_sgd_round", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
+    "moshpit_dynamic_reset", "moshpit_dynamic_round", "moshpit_dynamic_keys", "moshpit_local_step", "moshpit_sgd_round", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
 ]
 
 
@@ -68,6 +68,9 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_dist_to_mean_subset.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.moshpit_group_keys.argtypes = [vp, i64, vp]
     lib.moshpit_schedule_mask.argtypes = [vp, ctypes.POINTER(_CSchedule), i64, i32, vp]
+    lib.moshpit_dynamic_reset.argtypes = [vp]
+    lib.moshpit_dynamic_round.argtypes = [vp, i64, ctypes.c_uint64, vp]
+    lib.moshpit_dynamic_keys.argtypes = [vp, vp]
     lib.moshpit_local_step.argtypes = [vp, vp, vp, i64, ctypes.c_float]
     lib.moshpit_sgd_round.argtypes = [vp, i64, vp, vp, i64, ctypes.c_float]
     lib.moshpit_random_groups_round.argtypes = [vp, i64, ctypes.c_uint64, i32, vp]
@@ -219,6 +222,18 @@ class Moshpit:
         if a.shape != (self.N,):
             raise ValueError("alive mask must have shape (N,)")
         return a, a.ctypes.data
+
+    def dynamic_reset(self) -> None:
+        self._check(self._lib.moshpit_dynamic_reset(self._h), "dynamic_reset")
+
+    def dynamic_round(self, t: int, seed: int, alive=None) -> None:
+        keep, ptr = self._alive_ptr(alive)
+        self._check(self._lib.moshpit_dynamic_round(self._h, t, seed, ptr), "dynamic_round")
+
+    def dynamic_keys(self) -> np.ndarray:
+        keys = np.zeros((self.N, max(self.d - 1, 0)), dtype=np.int32)
+        self._check(self._lib.moshpit_dynamic_keys(self._h, keys.ctypes.data if keys.size else None), "dynamic_keys")
+        return keys
 
     def _grad(self, G):
         X = self._state[0]

@@ -24,6 +24,7 @@ struct moshpit_ctx {
     uint8_t *d_round_mask = nullptr;   // N bytes, for moshpit_round(host mask)
     uint8_t *d_present = nullptr;      // N bytes, for moshpit_dist_to_mean_subset
     int32_t *d_perm = nullptr;         // N, peer list of the list-based rounds
+    int32_t *d_dyn = nullptr;          // chunk-index keys and their scratch (see dyn_layout)
     uint8_t *d_masks = nullptr;        // mask_rounds_cap * N bytes, for runs
     int64_t mask_rounds_cap = 0;
     int32_t *d_keys = nullptr;         // N
@@ -206,6 +207,7 @@ int moshpit_destroy(moshpit_ctx *h)
     if (h->d_round_mask) (void)hipFree(h->d_round_mask);
     if (h->d_present) (void)hipFree(h->d_present);
     if (h->d_perm) (void)hipFree(h->d_perm);
+    if (h->d_dyn) (void)hipFree(h->d_dyn);
     if (h->d_masks) (void)hipFree(h->d_masks);
     if (h->d_keys) (void)hipFree(h->d_keys);
     if (h->d_partials) (void)hipFree(h->d_partials);
@@ -446,6 +448,82 @@ int moshpit_local_step(moshpit_ctx *h, const uint8_t *alive_host, const void *gr
     if (rc != MOSHPIT_OK) return rc;
     HIP_TRY(h, launch_local_step(h->X, h->dtype, h->N, h->P, h->row_stride, grad_dev, grad_row_stride_elems,
                                  alive_dev, gamma, h->stream));
+    return MOSHPIT_OK;
+}
+
+namespace {
+// one allocation: [keys N*(d-1)][packed N][count K+1][first K+1][index n_index]
+struct DynLayout {
+    int64_t kd, n_keys, n_index;
+    int32_t *keys, *packed, *count, *first, *index;
+};
+
+DynLayout dyn_layout(const moshpit_ctx *h)
+{
+    DynLayout L;
+    L.kd = h->d - 1;
+    L.n_keys = 1;
+    for (int q = 0; q < L.kd; ++q) L.n_keys *= h->M;
+    L.n_index = (h->N / h->M + L.n_keys) * h->M;
+    L.keys = h->d_dyn;
+    L.packed = L.keys + h->N * L.kd;
+    L.count = L.packed + h->N;
+    L.first = L.count + (L.n_keys + 1);
+    L.index = L.first + (L.n_keys + 1);
+    return L;
+}
+
+int dyn_ensure(moshpit_ctx *h)
+{
+    if (h->N > 65536) return fail(h, MOSHPIT_EINVAL, "chunk-index keys support at most 65536 peers");
+    if (h->d_dyn) return MOSHPIT_OK;
+    DynLayout L = dyn_layout(h);
+    const size_t words = static_cast<size_t>(h->N * L.kd + h->N + 2 * (L.n_keys + 1) + L.n_index);
+    HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_dyn), words * sizeof(int32_t)));
+    L = dyn_layout(h);
+    HIP_TRY(h, launch_dynamic_init(h->N, h->M, h->d, L.keys, h->stream));
+    return MOSHPIT_OK;
+}
+}  // namespace
+
+int moshpit_dynamic_reset(moshpit_ctx *h)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    if (h->d_dyn) {
+        HIP_TRY(h, launch_dynamic_init(h->N, h->M, h->d, dyn_layout(h).keys, h->stream));
+        return MOSHPIT_OK;
+    }
+    return dyn_ensure(h);
+}
+
+int moshpit_dynamic_round(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *alive_host)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
+    rc = dyn_ensure(h);
+    if (rc != MOSHPIT_OK) return rc;
+    const uint8_t *alive_dev = stage_mask(h, alive_host, &rc);
+    if (rc != MOSHPIT_OK) return rc;
+    const DynLayout L = dyn_layout(h);
+    HIP_TRY(h, launch_dynamic_grouping(h->N, h->M, h->d, seed, t, alive_dev, L.keys, L.packed, L.count, L.first,
+                                       L.index, L.n_index, h->stream));
+    RoundGeom geom{h->N, h->M, 1, L.index, L.n_index};
+    HIP_TRY(h, launch_group_mean(h->X, h->dtype, h->P, h->row_stride, geom, nullptr, h->tune, h->stream));
+    return MOSHPIT_OK;
+}
+
+int moshpit_dynamic_keys(moshpit_ctx *h, int32_t *keys_host)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    if (!keys_host && h->d > 1) return fail(h, MOSHPIT_EINVAL, "keys output is NULL");
+    int rc = dyn_ensure(h);
+    if (rc != MOSHPIT_OK) return rc;
+    const DynLayout L = dyn_layout(h);
+    if (L.kd > 0)
+        HIP_TRY(h, hipMemcpyAsync(keys_host, L.keys, sizeof(int32_t) * static_cast<size_t>(h->N * L.kd),
+                                  hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
     return MOSHPIT_OK;
 }
 

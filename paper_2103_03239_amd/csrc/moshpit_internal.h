@@ -60,6 +60,16 @@ hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, i
 hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down, int64_t N, int64_t t0,
                            int rounds, uint8_t *masks, hipStream_t stream);
 
+// Alg. 1 with chunk-index keys.  keys: device, N x (d-1) int32.  init writes the initial
+// keys; grouping turns (keys, alive, seed, t) into the padded peer list index[0..n_index)
+// (group g = entries [g*M, (g+1)*M), unused entries -1; n_index >= (N/M + M^(d-1)) * M) and
+// shifts each participant's chunk index into its key.  packed: N int32, count/first:
+// M^(d-1)+1 int32 each (device scratch).
+hipError_t launch_dynamic_init(int64_t N, int32_t M, int32_t d, int32_t *keys, hipStream_t stream);
+hipError_t launch_dynamic_grouping(int64_t N, int32_t M, int32_t d, uint64_t seed, int64_t t, const uint8_t *alive,
+                                   int32_t *keys, int32_t *packed, int32_t *count, int32_t *first, int32_t *index,
+                                   int64_t n_index, hipStream_t stream);
+
 // Queue the group-skip filter on masks[rounds][N] (device, in place) for rounds t0..
 hipError_t launch_skip_filter(uint8_t *masks, int64_t N, int32_t M, int32_t d, int64_t t0, int rounds,
                               hipStream_t stream);

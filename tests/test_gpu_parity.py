@@ -553,3 +553,36 @@ def test_user_stream_and_two_handles():
         mb.sync()
     assert_state_close(to_f64(A), ref_a, TOL[0], "stream a")
     assert_state_close(to_f64(B), ref_b, TOL[1], "stream b")
+
+
+# --------------------------------------------------------------------------
+# Alg. 1 with chunk-index keys
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,d,P,dtype,p", [(32, 2, 1_000, 0, 0.05), (16, 3, 264, 1, 0.1), (4, 3, 3_001, 0, 0.3),
+                                           (3, 4, 96, 0, 0.2), (2, 5, 512, 1, 0.0), (8, 1, 100, 0, 0.25),
+                                           (7, 2, 4_096, 0, 0.0)])
+def test_dynamic_key_rounds(M, d, P, dtype, p):
+    N, rounds, seed = M ** d, 2 * d + 2, 1234
+    w = inputs.Workload("dynamic", N, M, d, P, dtype, "peer_offset", 1, p, 0, rounds, 91, 92)
+    say(f"chunk-index keys {w}")
+    X = inputs.make_state(w, DEV, row_stride=P + (8 - P % 8) % 8)
+    X0 = to_f64(X).copy()
+    ref = X0.copy()
+    keys = orc.dynamic_init(N, M, d)
+    masks = orc.schedule_masks(1, p, 92, 0, N, 0, rounds)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(X)
+        assert np.array_equal(m.dynamic_keys(), keys)
+        for t in range(rounds):
+            alive = masks[t] if p > 0 else None
+            m.dynamic_round(t, seed, alive)
+            orc.dynamic_round(ref, M, d, keys, seed, t, alive)
+            assert np.array_equal(m.dynamic_keys(), keys), f"keys differ after round {t}"
+            if p == 0 and t == d - 1:
+                m.sync()
+                assert_state_close(to_f64(X), np.broadcast_to(X0.mean(axis=0), X0.shape), TOL[dtype], "exact mean")
+        m.sync()
+        assert_state_close(to_f64(X), ref, TOL[dtype], w.name)
+        m.dynamic_reset()
+        assert np.array_equal(m.dynamic_keys(), orc.dynamic_init(N, M, d))
