@@ -15,11 +15,17 @@
 // over a balanced tree of 16-position blocks, blocks added in ascending order,
 // one division by the participant count.
 //
-// Schedule.  One persistent block of 1024 threads per compute unit (the tile
-// takes most of the 160 KiB of LDS).  While the rounds of tile k run in LDS the
-// 128-bit loads of tile k+1 are already in flight into registers, and the
-// stores of tile k drain while tile k+1 is being set up, so HBM time and LDS
-// arithmetic overlap.
+// Schedule.  Persistent blocks, 16 waves per compute unit: two blocks of 512
+// threads with 80 KiB of LDS each, or, when that lets more axes be fused, one
+// block of 1024 threads with 160 KiB.  A thread owns 8 tile slots of 16 bytes
+// (512 * 8 * 16 B = 64 KiB, or 128 KiB, of tile).  While the rounds of tile k
+// run in LDS the 128-bit loads of tile k+1 are in flight into registers;
+// afterwards every thread swaps its slots (tile k to HBM, tile k+1 into LDS)
+// and the stores drain during the rounds of tile k+1.  A wave that issues
+// vector memory instructions faster than the compute unit's share of HBM
+// delivers stalls at the issue stage, and the round barriers pass that stall to
+// the whole block; two blocks out of step with each other are what overlaps
+// memory time with arithmetic.
 //
 // LDS layout (dynamic): [tile: rows x Wb bytes][2 x bitmaps: rounds x groups
 // u64][byte offset of every local row][2 x row flags: rows bytes][first local
@@ -33,15 +39,28 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 1024;
-constexpr int kLdsBytes = 160 * 1024;
-constexpr int kPrefetch = 10;         // 128-bit vectors per thread: 1024 * 10 * 16 B = 160 KiB
+// BPC = blocks per compute unit (1 or 2): a block has 1024 / BPC threads and
+// 160 / BPC KiB of LDS, so a compute unit always runs 16 waves on one or two tiles.
+constexpr int threads_of(int bpc) { return 1024 / bpc; }
+constexpr int lds_of(int bpc) { return 160 * 1024 / bpc; }
+constexpr int kMinSeg = 128;          // fewest bytes of a row in a tile
+constexpr int kPrefetch = 8;          // 128-bit vectors per thread: 1024 * 8 * 16 B = 128 KiB of tile
 
 __device__ __forceinline__ uint32_t bf16_bits_rne(float f)
 {
     uint32_t u = __float_as_uint(f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Block barrier that orders LDS traffic only.  __syncthreads() also waits for
+// every outstanding global load and store of the wave (its fence covers global
+// memory), which would serialise the tile prefetch and the store drain with
+// the rounds running in LDS.  Threads of a block exchange data through LDS
+// only, so waiting for the LDS counter before the barrier is sufficient.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // CV consecutive columns of one row in LDS, widened to binary32.
@@ -192,9 +211,11 @@ __device__ __forceinline__ void tree_block(const typename Cols<DT, CV>::elem_t *
 // CV = columns one thread averages at a time; SPLIT = lanes of a wave that share
 // the positions of one group (chosen so that every thread has work even when
 // the tile is narrow).
-template <int DT, int TREE, int CV, int SPLIT, int PER>
-__global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const uint8_t *__restrict__ masks, FusedPlan p)
+template <int DT, int TREE, int CV, int SPLIT, int PER, int BPC>
+__global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu(4, 4))) void fused_rounds_kernel(
+    char *X, const uint8_t *__restrict__ masks, FusedPlan p)
 {
+    constexpr int kThreads = threads_of(BPC);
     typedef Cols<DT, CV> Q;
     typedef typename Q::elem_t elem_t;
     constexpr int FLAT = 16 / CV;
@@ -225,15 +246,15 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
     // so a buffer is rebuilt only when the block moves to another sub-grid.
     // One thread per (round, row): independent byte loads, bits merged with LDS
     // atomics.
-    int64_t tag[2] = {-1, -1};
+    int64_t tag0 = -1, tag1 = -1;                    // sub-grid held by buffer 0 / 1
     auto prepare = [&](const TileRef &t, int buf) {
-        if (tag[buf] == t.plane) return;
-        tag[buf] = t.plane;
+        if ((buf == 0 ? tag0 : tag1) == t.plane) return;
+        if (buf == 0) tag0 = t.plane; else tag1 = t.plane;
         unsigned long long *bm = reinterpret_cast<unsigned long long *>(bitmaps0 + buf * bm_count);
         uint8_t *flag = rowflag0 + buf * p.rows_padded;
         for (int32_t i = tid; i < bm_count; i += kThreads) bm[i] = 0ull;
         for (int32_t lr = tid; lr < p.rows; lr += kThreads) flag[lr] = 0;
-        __syncthreads();
+        lds_barrier();
         const int32_t pairs = p.rounds * p.rows;
         constexpr int kB = 8;
         for (int32_t i0 = tid; i0 < pairs; i0 += kThreads * kB) {
@@ -264,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
                 }
             }
         }
-        __syncthreads();
+        lds_barrier();
     };
 
     // Slot b of a thread is vector idx = tid + b * kThreads of the tile, i.e.
@@ -273,31 +294,41 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
     // having all of it hoisted into registers that live across the rounds.
     const int32_t slot_dq = kThreads / Wv, slot_dr = kThreads - slot_dq * Wv;
 
-    // Issue the tile's 128-bit loads into registers; returns the mask of slots in use.
+    // Issue the 128-bit loads of slots [b_lo, b_hi) of a tile into registers and
+    // add them to the mask of slots in use.  The load is written as an asm
+    // statement so that the compiler does not track it: for a load of its own,
+    // issued in a loop into a register that an earlier iteration may have left
+    // pending, it waits for ALL memory traffic first, which would serialise
+    // every load behind the stores of the previous tile.  In exchange the wait
+    // is ours to place: nothing may read or copy pre[] between fetch() and the
+    // vmcnt(0) wait that precedes the swap (each pre[b] is an in-out operand, so
+    // the load lands in the register that holds the variable).
     u32x4 pre[kPrefetch];
-    auto fetch = [&](const TileRef &t, int buf) -> uint32_t {
+#pragma unroll
+    for (int b = 0; b < kPrefetch; ++b) pre[b] = u32x4{0u, 0u, 0u, 0u};
+    auto fetch = [&](const TileRef &t, int buf, int b_lo, int b_hi, uint32_t &used) {
         const uint8_t *flag = rowflag0 + buf * p.rows_padded;
         const int32_t seg_vec = t.seg_bytes / 16;
         const char *origin = X + t.base * p.row_bytes + t.col0_bytes;
         int32_t t_ = tid;
         asm volatile("" : "+v"(t_));
         int32_t lr = t_ / Wv, v = t_ - lr * Wv;
-        uint32_t used = 0;
 #pragma unroll
         for (int b = 0; b < kPrefetch; ++b) {
-            if (lr < p.rows && v < seg_vec && flag[lr]) {
-                pre[b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(origin + rowoff[lr] + v * 16));
+            if (b >= b_lo && b < b_hi && lr < p.rows && v < seg_vec && flag[lr]) {
+                const char *src = origin + rowoff[lr] + v * 16;
+                asm volatile("global_load_dwordx4 %0, %1, off nt" : "+v"(pre[b]) : "v"(src));
                 used |= 1u << b;
             }
             v += slot_dr;
             lr += slot_dq;
             if (v >= Wv) { v -= Wv; lr += 1; }
         }
-        return used;
     };
 
     // The fused rounds of one tile, in LDS, with the bitmaps of buffer `buf`.
-    auto compute = [&](const TileRef &t, int buf) {
+    // after_round(r) runs once the barrier of round r has been passed.
+    auto compute = [&](const TileRef &t, int buf, auto after_round) {
         const uint64_t *bm = bitmaps0 + buf * bm_count;
         const int32_t cchunks = t.seg_bytes / (CV * static_cast<int32_t>(sizeof(elem_t)));
         elem_t *T = reinterpret_cast<elem_t *>(tile);
@@ -384,54 +415,58 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
                 gl += dg;
                 if (cc >= cchunks) { cc -= cchunks; gl += 1; }
             }
-            __syncthreads();
+            lds_barrier();
+            after_round(r);
         }
     };
 
-    // Software pipeline over the block's tiles k = 0, 1, 2, ...:
-    //   while tile k is averaged in LDS, the loads of tile k+1 are in flight into
-    //   `pre`; afterwards tile k leaves LDS for HBM and tile k+1 enters LDS from
-    //   `pre`, the loads of tile k+2 are issued, and tile k+1 is averaged while
-    //   both drain.  The mask reads of prepare() come before the stores are
-    //   issued, so waiting for them never waits for a store.
+    // Software pipeline over the block's tiles k = 0, 1, 2, ...  While tile k is
+    // averaged in LDS, the loads of tile k+1 are issued into `pre` (before the
+    // first round, or in `spread` portions after the first rounds).  Afterwards
+    // tile k leaves LDS for HBM and tile k+1 enters LDS from `pre`; the stores
+    // drain while tile k+1 is averaged.
     const int64_t stride = gridDim.x;
     int64_t w = blockIdx.x;
     if (w >= p.work_items) return;
     TileRef cur = tile_ref(p, w);
     int buf_cur = 0;
     prepare(cur, buf_cur);
-    uint32_t used_cur = fetch(cur, buf_cur);
+    uint32_t used_cur = 0;
+    fetch(cur, buf_cur, 0, kPrefetch, used_cur);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int b = 0; b < kPrefetch; ++b) asm volatile("" : "+v"(pre[b]));
 #pragma unroll
     for (int b = 0; b < kPrefetch; ++b)
         if (used_cur & (1u << b)) *reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(tid + b * kThreads) * 16) = pre[b];
-    __syncthreads();
-    bool has_next = w + stride < p.work_items;
-    TileRef nxt = cur;
-    int buf_next = buf_cur;
-    uint32_t used_next = 0;
-    if (has_next) {
-        nxt = tile_ref(p, w + stride);
-        buf_next = nxt.plane == cur.plane ? buf_cur : buf_cur ^ 1;
-        prepare(nxt, buf_next);
-        used_next = fetch(nxt, buf_next);
-    }
+    lds_barrier();
 
     while (true) {
-        compute(cur, buf_cur);
-
-        const bool has_next2 = has_next && (w + 2 * stride < p.work_items);
-        TileRef nn = nxt;
-        int buf_nn = buf_next;
-        if (has_next2) {
-            nn = tile_ref(p, w + 2 * stride);
-            // the other buffer is free: it held tile k's sub-grid (done) or nothing
-            buf_nn = nn.plane == nxt.plane ? buf_next : buf_next ^ 1;
-            prepare(nn, buf_nn);
+        const bool has_next = w + stride < p.work_items;
+        TileRef nxt = cur;
+        int buf_next = buf_cur;
+        uint32_t used_next = 0;
+        if (has_next) {
+            nxt = tile_ref(p, w + stride);
+            buf_next = nxt.plane == cur.plane ? buf_cur : buf_cur ^ 1;
+            prepare(nxt, buf_next);
         }
+        // spread == 0: all slots of tile k+1 before the first round; otherwise slots
+        // [r * kPrefetch / spread, (r + 1) * kPrefetch / spread) after round r < spread
+        const int32_t spread = p.rounds < p.spread ? p.rounds : p.spread;
+        if (has_next && p.spread == 0) fetch(nxt, buf_next, 0, kPrefetch, used_next);
+        compute(cur, buf_cur, [&](int32_t r) {
+            if (has_next && r < spread)
+                fetch(nxt, buf_next, r * kPrefetch / spread, (r + 1) * kPrefetch / spread, used_next);
+        });
+
+        // Wait for the loads of tile k+1 (and, in passing, for the stores of tile
+        // k-1); the empty asm statements keep every use of pre[] below the wait.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int b = 0; b < kPrefetch; ++b) asm volatile("" : "+v"(pre[b]));
         // Each thread owns the same tile slots for every tile, so it swaps tile
-        // k out of LDS and tile k+1 in, slot by slot, without a barrier; the
-        // stores are issued only afterwards so that waiting for the loads of
-        // tile k+1 never waits for a store.
+        // k out of LDS and tile k+1 in, slot by slot, without a barrier.
         constexpr int kHalf = kPrefetch / 2;
         {
             char *origin = X + cur.base * p.row_bytes + cur.col0_bytes;
@@ -446,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
                     const int b = h * kHalf + q;
                     u32x4 *slot = reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(t_ + b * kThreads) * 16);
                     if (used_cur & (1u << b)) val[q] = *slot;
-                    if (has_next && (used_next & (1u << b))) *slot = pre[b];
+                    if (used_next & (1u << b)) *slot = pre[b];
                 }
 #pragma unroll
                 for (int q = 0; q < kHalf; ++q) {
@@ -460,17 +495,11 @@ __global__ __launch_bounds__(kThreads) void fused_rounds_kernel(char *X, const u
             }
         }
         if (!has_next) break;
-        __syncthreads();
-        uint32_t used_nn = 0;
-        if (has_next2) used_nn = fetch(nn, buf_nn);
+        lds_barrier();
         w += stride;
         cur = nxt;
         used_cur = used_next;
         buf_cur = buf_next;
-        nxt = nn;
-        used_next = used_nn;
-        buf_next = buf_nn;
-        has_next = has_next2;
     }
 }
 
@@ -484,9 +513,13 @@ int64_t fixed_lds(int64_t rounds, int64_t rows, int64_t groups, int64_t F)
 
 }  // namespace
 
-bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t row_stride, const void *X,
-                int64_t t0, int32_t rounds_wanted, FusedPlan *out)
+namespace {
+
+bool plan_with(int bpc, int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t row_stride, const void *X,
+               int64_t t0, int32_t rounds_wanted, FusedPlan *out)
 {
+    const int kThreads = threads_of(bpc);
+    const int kLdsBytes = lds_of(bpc);
     const int64_t esize = dtype == 0 ? 4 : 2;
     const int64_t row_bytes = row_stride * esize;
     const int64_t valid = P * esize;
@@ -499,7 +532,8 @@ bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t r
     while (F < d && F < rounds_wanted && F < kFusedMaxAxes) {
         const int64_t next = rows * M;
         const int64_t min_rounds = (F + 1 == d) ? 2 : (F + 1);
-        if (next * 128 + fixed_lds(min_rounds, next, next / M, F + 1) > kLdsBytes) break;
+        if (next * kMinSeg + fixed_lds(min_rounds, next, next / M, F + 1) > kLdsBytes) break;
+        if (next * kMinSeg > static_cast<int64_t>(kThreads) * kPrefetch * 16) break;
         rows = next;
         ++F;
     }
@@ -542,10 +576,18 @@ bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t r
         if (rounds < 2) return false;
     }
     p.rounds = rounds;
+    // When the loads of the next tile are issued (measured on MI355X): a block
+    // that has the compute unit to itself and many rounds to run does best
+    // issuing them in four portions, after each of the first four rounds;
+    // otherwise all of them before the first round.
+    p.spread = (bpc == 1 && rounds >= 4) ? 4 : 0;
     const int64_t fixed = fixed_lds(rounds, rows, p.groups, F);
-    int64_t wb = (kLdsBytes - fixed) / rows;
-    wb = wb >= 128 ? wb / 128 * 128 : 0;
-    if (wb < 128) return false;
+    int64_t budget = kLdsBytes - fixed;                          // LDS left for the tile ...
+    const int64_t reg_tile = static_cast<int64_t>(kThreads) * kPrefetch * 16;   // ... and what the prefetch registers hold
+    if (budget > reg_tile) budget = reg_tile;
+    int64_t wb = budget / rows;
+    wb = wb >= kMinSeg ? wb / kMinSeg * kMinSeg : 0;
+    if (wb < kMinSeg) return false;
     if (wb > valid) wb = valid;                  // a multiple of 16 (checked above)
     // small states: narrower tiles so that every compute unit gets a few of them
     const int64_t planes_total = N / rows;
@@ -557,22 +599,44 @@ bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t r
     p.tiles = (valid + wb - 1) / wb;
     p.planes = N / rows;
     p.work_items = p.planes * p.tiles;
+    p.blocks_per_cu = bpc;
     *out = p;
     return true;
 }
 
-hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const uint8_t *masks, hipStream_t stream)
+}  // namespace
+
+// Two blocks per compute unit run out of step with each other, which hides a
+// good part of the time a block spends issuing its loads and stores; one block
+// per compute unit has twice the LDS for its tile and is taken when that lets
+// more axes be fused (M^F rows of >= 128 bytes must fit).
+bool plan_fused(int dtype, int64_t N, int32_t M, int32_t d, int64_t P, int64_t row_stride, const void *X,
+                int64_t t0, int32_t rounds_wanted, FusedPlan *out)
 {
+    FusedPlan two{}, one{};
+    const bool ok2 = plan_with(2, dtype, N, M, d, P, row_stride, X, t0, rounds_wanted, &two);
+    const bool ok1 = plan_with(1, dtype, N, M, d, P, row_stride, X, t0, rounds_wanted, &one);
+    if (!ok1 && !ok2) return false;
+    *out = (ok2 && (!ok1 || two.F >= one.F)) ? two : one;
+    return true;
+}
+
+namespace {
+
+template <int BPC>
+hipError_t launch_with(void *X, int dtype, const FusedPlan &plan, const uint8_t *masks, hipStream_t stream)
+{
+    constexpr int kThreads = threads_of(BPC);
     typedef void (*kernel_t)(char *, const uint8_t *, FusedPlan);
     // shape index: 0..2 = 1, 2, 4 columns per thread; 3..6 = 4 columns per thread with
-    // (lanes per item, positions per lane) = (2,8) (2,16) (4,4) (4,8)
-#define MOSHPIT_ROW(DT, TR)                                                                                       \
-    {fused_rounds_kernel<DT, TR, 1, 1, 0>, fused_rounds_kernel<DT, TR, 2, 1, 0>, fused_rounds_kernel<DT, TR, 4, 1, 0>, \
-     nullptr, nullptr, nullptr, nullptr}
-#define MOSHPIT_ROW16(DT)                                                                                         \
-    {fused_rounds_kernel<DT, 16, 1, 1, 0>, fused_rounds_kernel<DT, 16, 2, 1, 0>, fused_rounds_kernel<DT, 16, 4, 1, 0>, \
-     fused_rounds_kernel<DT, 16, 4, 2, 8>, fused_rounds_kernel<DT, 16, 4, 2, 16>,                                  \
-     fused_rounds_kernel<DT, 16, 4, 4, 4>, fused_rounds_kernel<DT, 16, 4, 4, 8>}
+    // (lanes per item, positions per lane) = (2,8) (unused) (4,4) (4,8)
+#define MOSHPIT_ROW(DT, TR)                                                                                   \
+    {fused_rounds_kernel<DT, TR, 1, 1, 0, BPC>, fused_rounds_kernel<DT, TR, 2, 1, 0, BPC>,                    \
+     fused_rounds_kernel<DT, TR, 4, 1, 0, BPC>, nullptr, nullptr, nullptr, nullptr}
+#define MOSHPIT_ROW16(DT)                                                                                     \
+    {fused_rounds_kernel<DT, 16, 1, 1, 0, BPC>, fused_rounds_kernel<DT, 16, 2, 1, 0, BPC>,                    \
+     fused_rounds_kernel<DT, 16, 4, 1, 0, BPC>, fused_rounds_kernel<DT, 16, 4, 2, 8, BPC>, nullptr,           \
+     fused_rounds_kernel<DT, 16, 4, 4, 4, BPC>, fused_rounds_kernel<DT, 16, 4, 4, 8, BPC>}
     static const kernel_t table[2][4][7] = {
         {MOSHPIT_ROW(0, 2), MOSHPIT_ROW(0, 4), MOSHPIT_ROW(0, 8), MOSHPIT_ROW16(0)},
         {MOSHPIT_ROW(1, 2), MOSHPIT_ROW(1, 4), MOSHPIT_ROW(1, 8), MOSHPIT_ROW16(1)}};
@@ -591,8 +655,9 @@ hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const 
     if (items4 < kThreads) {
         if (ti == 3 && plan.M <= 32) {
             const bool two_blocks = plan.M > 16;
-            if (items4 * 2 >= kThreads) ci = two_blocks ? 4 : 3;
-            else ci = two_blocks ? 6 : 5;
+            // (two 16-position blocks over 2 lanes would need 16 positions per lane: too many registers)
+            if (two_blocks) ci = 6;
+            else ci = items4 * 2 >= kThreads ? 3 : 5;
         } else {
             while (ci > 0 && plan.groups * (cols >> ci) < kThreads) --ci;
         }
@@ -600,7 +665,7 @@ hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const 
     const kernel_t kernel = table[dtype][ti][ci];
     if (!raised[dtype][ti][ci]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_of(BPC));
         if (e != hipSuccess) return e;
         raised[dtype][ti][ci] = true;
     }
@@ -611,11 +676,21 @@ hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const 
         if (e != hipSuccess) return e;
         if (compute_units <= 0) compute_units = 256;
     }
-    // persistent: one block per compute unit walks the tiles
-    const int64_t grid = plan.work_items < compute_units ? plan.work_items : compute_units;
+    // persistent: BPC blocks per compute unit walk the tiles
+    const int64_t slots = static_cast<int64_t>(compute_units) * BPC;
+    const int64_t grid = plan.work_items < slots ? plan.work_items : slots;
     kernel<<<dim3(static_cast<uint32_t>(grid)), dim3(kThreads), plan.lds_bytes, stream>>>(static_cast<char *>(X), masks,
                                                                                          plan);
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const uint8_t *masks, hipStream_t stream)
+{
+    if (plan.blocks_per_cu == 2) return launch_with<2>(X, dtype, plan, masks, stream);
+    if (plan.blocks_per_cu == 1) return launch_with<1>(X, dtype, plan, masks, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace moshpit

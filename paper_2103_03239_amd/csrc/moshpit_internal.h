@@ -90,6 +90,8 @@ struct FusedPlan {
     int32_t rows, groups;          // M^F rows per tile, rows / M groups per round
     int32_t rows_padded;           // rows rounded up to a multiple of 16
     int32_t rounds;                // rounds fused by this pass
+    int32_t blocks_per_cu;         // 1 or 2: which kernel shape the plan was made for
+    int32_t spread;                // the next tile's loads are issued in this many portions, one per round
     int32_t local_axis0;           // tile-local axis of the first round
     int32_t n_outer;               // grid axes outside the tile
     int32_t Wb, tile_bytes, lds_bytes;
