@@ -28,8 +28,8 @@
 // memory time with arithmetic.
 //
 // LDS layout (dynamic): [tile: rows x Wb bytes][2 x bitmaps: rounds x groups
-// u64][byte offset of every local row][2 x row flags: rows bytes][first local
-// row of every group per axis].
+// u64][byte offset of every local row][2 x row flags: rows bytes][tile offset of
+// the first row of every group per axis][pad][16 bytes of zeros][16 bytes of write-only trash].
 #include "moshpit_internal.h"
 
 namespace moshpit {
@@ -61,6 +61,24 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float f)
 __device__ __forceinline__ void lds_barrier()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// x + (x of the lane 16 / 32 lanes away, lane index xor 16 / 32), without a
+// trip through LDS: the swap instructions exchange rows of 16 (halves of 32)
+// lanes between their two operands, after which each operand holds one of the
+// two addends in every lane.  Addition commutes, so both partners get the same
+// bits.
+__device__ __forceinline__ float add_across_16(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane16_swap(b, b, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float add_across_32(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 // CV consecutive columns of one row in LDS, widened to binary32.
@@ -172,28 +190,29 @@ __device__ __forceinline__ TileRef tile_ref(const FusedPlan &p, int64_t w)
 }
 
 // Sum of TREE positions j0..j0+TREE-1 of CV columns of a group, as the balanced
-// tree ((x0+x1)+(x2+x3))+...; positions whose bit is clear contribute an exact
-// 0.  Blocks of up to FLAT positions are read at once; larger trees are the sum
-// of their two balanced halves, which bounds the register footprint.
+// tree ((x0+x1)+(x2+x3))+...; positions whose bit is clear (absent peers, and
+// positions past the group, whose bits are never set) contribute an exact 0:
+// their read is redirected to `zeros`, 16 bytes of LDS that hold 0, which costs
+// one select per position instead of one per value.  Blocks of up to FLAT
+// positions are read at once; larger trees are the sum of their two balanced
+// halves, which bounds the register footprint.
 template <int DT, int CV, int TREE, int FLAT>
 __device__ __forceinline__ void tree_block(const typename Cols<DT, CV>::elem_t *col, int32_t step, int32_t j0,
-                                           int32_t M, uint32_t bits, float (&out)[CV])
+                                           const typename Cols<DT, CV>::elem_t *zeros, uint32_t bits,
+                                           float (&out)[CV])
 {
     if constexpr (TREE > FLAT) {
         float lo[CV], hi[CV];
-        tree_block<DT, CV, TREE / 2, FLAT>(col, step, j0, M, bits & ((1u << (TREE / 2)) - 1u), lo);
-        tree_block<DT, CV, TREE / 2, FLAT>(col, step, j0 + TREE / 2, M, bits >> (TREE / 2), hi);
+        tree_block<DT, CV, TREE / 2, FLAT>(col, step, j0, zeros, bits & ((1u << (TREE / 2)) - 1u), lo);
+        tree_block<DT, CV, TREE / 2, FLAT>(col, step, j0 + TREE / 2, zeros, bits >> (TREE / 2), hi);
 #pragma unroll
         for (int e = 0; e < CV; ++e) out[e] = lo[e] + hi[e];
     } else {
         float f[TREE][CV];
 #pragma unroll
         for (int u = 0; u < TREE; ++u) {
-            const int32_t j = (j0 + u) < M ? (j0 + u) : (M - 1);      // never read past the group
-            Cols<DT, CV>::load(col + j * step, f[u]);
             const bool on = (bits >> u) & 1u;
-#pragma unroll
-            for (int e = 0; e < CV; ++e) f[u][e] = on ? f[u][e] : 0.f;
+            Cols<DT, CV>::load(on ? col + (j0 + u) * step : zeros, f[u]);
         }
 #pragma unroll
         for (int s = 1; s < TREE; s *= 2)
@@ -226,6 +245,8 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
     int64_t *rowoff = reinterpret_cast<int64_t *>(bitmaps0 + 2 * bm_count);      // byte offset of local row lr
     uint8_t *rowflag0 = reinterpret_cast<uint8_t *>(rowoff + p.rows_padded);
     int32_t *lbase_tab = reinterpret_cast<int32_t *>(rowflag0 + 2 * p.rows_padded);
+    elem_t *zeros = reinterpret_cast<elem_t *>(lds + p.lds_bytes - 32);            // 16 bytes that hold 0
+    elem_t *trash = reinterpret_cast<elem_t *>(lds + p.lds_bytes - 16);            // 16 bytes nobody reads
 
     const int tid = threadIdx.x;
 
@@ -234,9 +255,10 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
         const int32_t f = i / p.groups, gl = i - f * p.groups;
         int32_t Sl = 1;
         for (int q = 0; q < f; ++q) Sl *= p.M;
-        lbase_tab[i] = (gl / Sl) * Sl * p.M + (gl % Sl);
+        lbase_tab[i] = ((gl / Sl) * Sl * p.M + (gl % Sl)) * p.Wb;        // as a byte offset into the tile
     }
     for (int32_t lr = tid; lr < p.rows; lr += kThreads) rowoff[lr] = global_row(p, 0, lr) * p.row_bytes;
+    if (tid < 4) reinterpret_cast<uint32_t *>(zeros)[tid] = 0u;
 
     const int32_t Wv = p.Wb / 16;
     const int32_t W = p.Wb / static_cast<int32_t>(sizeof(elem_t));     // columns of a full tile
@@ -331,7 +353,6 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
     auto compute = [&](const TileRef &t, int buf, auto after_round) {
         const uint64_t *bm = bitmaps0 + buf * bm_count;
         const int32_t cchunks = t.seg_bytes / (CV * static_cast<int32_t>(sizeof(elem_t)));
-        elem_t *T = reinterpret_cast<elem_t *>(tile);
         // SPLIT adjacent lanes share one (group, column chunk) item and take
         // SPLIT equal parts of its positions
         // (sub is the slow lane index, so 8 consecutive lanes read 128 contiguous
@@ -352,34 +373,52 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
             int32_t gl = g_first, cc = c_first;
             while (gl < p.groups) {
                 const uint64_t live = bmr[gl];
+                const int32_t lbase = lb[gl];          // read together with the bitmap
                 const int cnt = __popcll(live);
                 if (cnt >= 2) {
-                    elem_t *col = T + static_cast<int64_t>(lb[gl]) * W + cc * CV;
+                    elem_t *col = reinterpret_cast<elem_t *>(tile + lbase) + cc * CV;
                     float acc[CV];
-                    uint64_t mine = live;              // positions this thread writes back
-                    int32_t wj0 = 0;                   // first position of this thread's part
 #pragma unroll
                     for (int e = 0; e < CV; ++e) acc[e] = 0.f;
+                    elem_t *pos[SPLIT > 1 ? PER : 1];  // where this thread's positions are written back (SPLIT > 1)
                     if constexpr (SPLIT > 1) {
                         // M <= 32 here: SPLIT * PER = 16 or 32 positions (one or two
                         // 16-position blocks) cut into SPLIT balanced sub-trees of PER
-                        // positions; the xor butterfly over the SPLIT lanes adds them in
-                        // the order of the full tree.
+                        // positions; the butterfly over the SPLIT lanes adds them in the
+                        // order of the full tree.  All PER row reads are issued before
+                        // the first use; the opaque copy of the row step keeps the
+                        // per-position addresses out of registers that live across items.
+                        int32_t st = step;
+                        asm volatile("" : "+s"(st));
                         const int32_t j0 = sub * PER;
-                        const uint32_t bits = static_cast<uint32_t>(live >> j0) & ((1u << PER) - 1u);
-                        mine = static_cast<uint64_t>(bits) << j0;
-                        wj0 = j0;
-                        float part[CV];
-                        tree_block<DT, CV, PER, FLAT>(col, step, j0, p.M, bits, part);
+                        const uint32_t pbits = static_cast<uint32_t>(live >> j0) & ((1u << PER) - 1u);
+                        elem_t *q = col + __mul24(j0, st);
+                        float f[PER][CV];
+#pragma unroll
+                        for (int u = 0; u < PER; ++u) {
+                            // absent peers and positions past the group read the zeros,
+                            // and their (unconditional) store goes to the trash
+                            const bool on = (pbits >> u) & 1u;
+                            Q::load(on ? q : zeros, f[u]);
+                            pos[u] = on ? q : trash;
+                            q += st;
+                        }
+#pragma unroll
+                        for (int w2 = 1; w2 < PER; w2 *= 2)
+#pragma unroll
+                            for (int u = 0; u + w2 < PER; u += 2 * w2)
+#pragma unroll
+                                for (int e = 0; e < CV; ++e) f[u][e] += f[u + w2][e];
 #pragma unroll
                         for (int e = 0; e < CV; ++e) {
-                            part[e] += __shfl_xor(part[e], kLanesPerSub, 64);                          // sub ^ 1
-                            if constexpr (SPLIT > 2) part[e] += __shfl_xor(part[e], 2 * kLanesPerSub, 64);  // sub ^ 2
-                            acc[e] += part[e];
+                            float part = f[0][e];
+                            if constexpr (SPLIT > 2) part = add_across_16(part);      // sub ^ 1
+                            part = add_across_32(part);                               // sub ^ 1 (SPLIT 2) or sub ^ 2
+                            acc[e] += part;
                         }
                     } else if constexpr (TREE < 16) {
                         float t0[CV];
-                        tree_block<DT, CV, TREE, FLAT>(col, step, 0, p.M, static_cast<uint32_t>(live), t0);
+                        tree_block<DT, CV, TREE, FLAT>(col, step, 0, zeros, static_cast<uint32_t>(live), t0);
 #pragma unroll
                         for (int e = 0; e < CV; ++e) acc[e] += t0[e];
                     } else {
@@ -387,7 +426,7 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
                             const uint32_t bits = static_cast<uint32_t>(live >> j0) & 0xffffu;
                             if (bits == 0) continue;
                             float t16[CV];
-                            tree_block<DT, CV, 16, FLAT>(col, step, j0, p.M, bits, t16);
+                            tree_block<DT, CV, 16, FLAT>(col, step, j0, zeros, bits, t16);
 #pragma unroll
                             for (int e = 0; e < CV; ++e) acc[e] += t16[e];
                         }
@@ -395,19 +434,23 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
                     const float k = static_cast<float>(cnt);
 #pragma unroll
                     for (int e = 0; e < CV; ++e) acc[e] = acc[e] / k;
-                    if constexpr (SPLIT > 1 || TREE < 16) {
-                        // at most 16 positions, starting at wj0: straight-line predicated stores
-                        constexpr int kSpan = SPLIT > 1 ? PER : TREE;
-                        const uint32_t wbits = static_cast<uint32_t>(mine >> wj0);
+                    if constexpr (SPLIT > 1) {
 #pragma unroll
-                        for (int u = 0; u < kSpan; ++u)
-                            if ((wbits >> u) & 1u) Q::store(col + (wj0 + u) * step, acc);
+                        for (int u = 0; u < PER; ++u) Q::store(pos[u], acc);
+                    } else if constexpr (TREE < 16) {
+                        // at most 8 positions: straight-line predicated stores
+                        const uint32_t wbits = static_cast<uint32_t>(live);
+#pragma unroll
+                        for (int u = 0; u < TREE; ++u)
+                            if ((wbits >> u) & 1u) Q::store(col + u * step, acc);
                     } else {
-                        uint64_t rem = mine;
-                        while (rem != 0) {
-                            const int j = __builtin_ctzll(rem);
-                            rem &= rem - 1;
-                            Q::store(col + j * step, acc);
+                        // unconditional stores, 16 positions at a time; those of absent
+                        // peers and of positions past the group go to the trash
+                        for (int32_t j0 = 0; j0 < p.M; j0 += 16) {
+                            const uint32_t wbits = static_cast<uint32_t>(live >> j0);
+#pragma unroll
+                            for (int u = 0; u < 16; ++u)
+                                Q::store(((wbits >> u) & 1u) ? col + (j0 + u) * step : trash, acc);
                         }
                     }
                 }
@@ -508,7 +551,8 @@ int tree_size(int32_t M) { return M > 8 ? 16 : M > 4 ? 8 : M > 2 ? 4 : 2; }
 int64_t fixed_lds(int64_t rounds, int64_t rows, int64_t groups, int64_t F)
 {
     const int64_t rows_padded = (rows + 15) / 16 * 16;
-    return 2 * rounds * groups * 8 + rows_padded * 8 + 2 * rows_padded + F * groups * 4 + 64;
+    // tables, slack, then (16-byte aligned) 16 bytes of zeros and 16 bytes of write-only trash
+    return (2 * rounds * groups * 8 + rows_padded * 8 + 2 * rows_padded + F * groups * 4 + 32 + 15) / 16 * 16 + 32;
 }
 
 }  // namespace

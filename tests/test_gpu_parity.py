@@ -300,6 +300,37 @@ def test_fused_equals_single_rounds_and_oracle(M, d, P, dtype, p, t0, rounds):
         assert (~have).any(), "expected at least one fused pass"
 
 
+@pytest.mark.parametrize("M,d,dtype", [(6, 2, 0), (12, 2, 0), (20, 2, 0), (10, 2, 1)])
+def test_fused_division_edge_values(M, d, dtype):
+    """Sums that are tiny (quotient subnormal), zero, huge or infinite: the fused kernel
+    must give the bits of the single-round kernel, NaN for NaN."""
+    N, P, rounds = M ** d, 2_048, 4
+    say(f"fused division edge values M={M} d={d} dtype={dtype}")
+    g = torch.Generator(device="cpu").manual_seed(4242 + M)
+    kind = torch.randint(0, 6, (1, P), generator=g).expand(N, P)       # one kind of value per column
+    x = torch.randn(N, P, generator=g, dtype=torch.float32)
+    scale = torch.ones(N, P)
+    scale[kind == 0] = 2.0 ** -130      # subnormal inputs
+    scale[kind == 1] = 2.0 ** -122      # normal inputs whose mean is subnormal for larger counts
+    scale[kind == 2] = 2.0 ** 120       # huge, finite sums
+    x = x * scale
+    x[kind == 3] = 0.0
+    x[(kind == 4) & (torch.rand(N, P, generator=g) < 0.01)] = float("inf")
+    A = x.to(torch.bfloat16 if dtype else torch.float32).to(DEV).contiguous()
+    B = A.clone()
+    sched = binding.Schedule(kind=inputs.KIND_IID, p=0.2, seed=77 + M)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(A)
+        m.run(0, rounds, sched)
+        m.bind_state(B)
+        m.run(0, rounds, sched, flags=binding.RUN_FUSED)      # whole grid in one tile: one fused pass
+    bits = torch.int16 if dtype else torch.int32
+    same = (A.view(bits) == B.view(bits)) | (torch.isnan(A) & torch.isnan(B))
+    assert bool(same.all()), f"{int((~same).sum())} elements differ in bits"
+    tiny = (A != 0) & (A.abs().float() < 2.0 ** -126)
+    assert bool(tiny.any()) and bool(torch.isinf(A).any() | torch.isnan(A).any())
+
+
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
 def test_fused_full_size_matches_single_rounds(cfg):
     """Full-size workloads: the fused path reproduces the single-round path bit for bit."""
