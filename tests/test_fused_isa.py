@@ -1,0 +1,87 @@
+"""Static check of the fused kernel's machine code (no GPU needed).
+
+The fused multi-round kernel issues its tile prefetch as asm statements that the
+compiler does not track, and waits for them itself (one `s_waitcnt vmcnt(0)`
+before the registers are used).  That is only correct if the compiler never
+reads, copies or overwrites a prefetch register between the load that targets it
+and that wait.  This test compiles the kernel file to gfx950 assembly with the
+library's flags and checks every instantiation:
+
+* no instruction uses a register that has a prefetch load pending (linear scan);
+* in the steady-state loop (everything after the first tile has entered LDS) the
+  prefetch registers appear only as load destinations and as sources of the LDS
+  writes that follow the wait;
+* no kernel uses scratch memory (a spill would count as vector memory traffic and
+  serialise the prefetch).
+"""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+import __graft_entry__ as entry
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+def _regs(line: str) -> set[int]:
+    body = line.split(";")[0]
+    out: set[int] = set()
+    for m in re.finditer(r"\bv\[(\d+):(\d+)\]", body):
+        out.update(range(int(m.group(1)), int(m.group(2)) + 1))
+    for m in re.finditer(r"\bv(\d+)\b", body):
+        out.add(int(m.group(1)))
+    return out
+
+
+LOAD = re.compile(r"global_load_dwordx4 v\[(\d+):(\d+)\], v\[(\d+):(\d+)\]")
+
+
+@pytest.mark.skipif(shutil.which(HIPCC) is None and not os.path.exists(HIPCC), reason="hipcc not available")
+def test_prefetch_registers_untouched_until_the_wait(tmp_path):
+    asm = tmp_path / "fused_rounds.s"
+    flags = [f for f in entry.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    subprocess.check_call([HIPCC, *flags, "-I", os.path.join(entry.ROOT, "include"), "-S", "--cuda-device-only",
+                           os.path.join(entry.CSRC, "fused_rounds.hip"), "-o", str(asm)],
+                          stderr=subprocess.DEVNULL)
+    text = asm.read_text().split("\n")
+    starts = [i for i, l in enumerate(text) if re.match(r"^_ZN7moshpit.*fused_rounds_kernel.*:", l)]
+    assert len(starts) >= 30, "expected every instantiation of the fused kernel in the assembly"
+    for s in starts:
+        e = s
+        while "s_endpgm" not in text[e]:
+            e += 1
+        K = text[s:e + 1]
+        name = text[s].split(":")[0]
+        assert not any("scratch_" in l for l in K), f"{name}: uses scratch memory"
+        loads = [i for i, l in enumerate(K) if "global_load_dwordx4" in l]
+        # 8 loads for the first tile, 8 before the rounds of a tile, 8 spread over its rounds
+        assert len(loads) == 24, f"{name}: expected three groups of 8 prefetch loads"
+        pre: set[int] = set()
+        for i in loads:
+            m = LOAD.search(K[i])
+            assert m, K[i]
+            pre.update(range(int(m.group(1)), int(m.group(2)) + 1))
+        assert len(pre) == 32, f"{name}: prefetch registers are not the same in both places"
+        # (a) linear scan: nothing touches a register whose load is pending
+        pending: set[int] = set()
+        for l in K:
+            m = LOAD.search(l)
+            if m:
+                assert not (set(range(int(m.group(3)), int(m.group(4)) + 1)) & pending), f"{name}: {l}"
+                pending.update(range(int(m.group(1)), int(m.group(2)) + 1))
+            elif "s_waitcnt vmcnt(0)" in l:
+                pending = set()
+            else:
+                assert not (_regs(l) & pending), f"{name}: touches a pending prefetch register: {l.strip()}"
+        # (b) steady state: from the barrier after the first tile's LDS writes to the end
+        w0 = next(i for i in range(loads[7], len(K)) if "s_waitcnt vmcnt(0)" in K[i])
+        b0 = next(i for i in range(w0, len(K)) if "s_barrier" in K[i])
+        w1 = max(i for i in range(len(K)) if "s_waitcnt vmcnt(0)" in K[i])
+        assert w1 > loads[-1], f"{name}: no wait after the loop's prefetch loads"
+        for i in range(b0, len(K)):
+            if not (_regs(K[i]) & pre) or "global_load_dwordx4" in K[i]:
+                continue
+            assert "ds_write_b128" in K[i] and i > w1, f"{name}: line {i}: {K[i].strip()}"
