@@ -108,6 +108,49 @@ def test_small_full_state(M, d, P, dtype, stride, offset, p):
         assert (pad == 512.0).all()
 
 
+@pytest.mark.parametrize("M,d,P,dtype,p", [(32, 2, 3_000, 0, 0.2), (16, 2, 5_000, 0, 0.05), (4, 3, 9_999, 0, 0.1),
+                                            (3, 3, 777, 0, 0.25), (16, 3, 520, 1, 0.1), (7, 2, 2_000, 1, 0.15),
+                                            (64, 1, 1_024, 0, 0.1), (2, 6, 1_030, 1, 0.3)])
+def test_each_round_within_rounding_of_the_quantized_oracle(M, d, P, dtype, p):
+    """Round by round, from the SAME stored input: the kernel's result against the
+    oracle's fp64 mean rounded once to the storage type.  The only differences
+    allowed are the kernel's binary32 summation (a tree of depth ceil(log2 M) within
+    blocks of 16 and up to 3 more additions across blocks: at most 8 roundings, each
+    <= 2^-24 of a partial sum, partial sums <= the sum of |x| over the group's
+    participants) and one unit in the last place of the storage type where the two
+    sums fall on different sides of a rounding boundary.  Rows that do not take part
+    must not change at all.  This localises an error to a round, a group and a
+    column, where the tolerance on whole runs cannot."""
+    N = M ** d
+    rounds = 2 * d
+    w = inputs.Workload(f"ulp-{M}-{d}-{P}", N, M, d, P, dtype, "peer_offset", inputs.KIND_IID, p, 0, rounds,
+                        4 + M + P, 40 + P)
+    say(f"case {w}")
+    X = inputs.make_state(w, DEV)
+    masks = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, N, 0, rounds)
+    ulp = 2.0 ** -23 if dtype == 0 else 2.0 ** -7          # spacing relative to the binade's lower end
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(X)
+        for t in range(rounds):
+            before = to_f64(X)
+            want = before.copy()
+            orc.round_(want, M, d, t, masks[t])
+            orc.quantize(want, dtype)
+            mean_abs = np.abs(before)
+            orc.round_(mean_abs, M, d, t, masks[t])        # group mean of |x| for participants
+            m.round(t, masks[t])
+            got = to_f64(X)
+            probe = np.random.default_rng(t).random((N, 1))
+            moved = probe.copy()
+            orc.round_(moved, M, d, t, masks[t])
+            outside = (moved == probe)[:, 0]                # absent peers and lone survivors
+            assert np.array_equal(got[outside], before[outside]), f"round {t}: a row outside the round changed"
+            bound = 8 * 2.0 ** -24 * mean_abs + ulp * np.abs(want) + 1e-300
+            bad = np.abs(got - want) > bound
+            assert not bad.any(), (f"round {t}: {int(bad.sum())} elements off by more than the rounding bound; "
+                                   f"first at {tuple(np.argwhere(bad)[0])}: got {got[bad][0]!r} want {want[bad][0]!r}")
+
+
 def test_workload1_is_exact_global_mean():
     """Full grid, no failures, d rounds: every peer ends on the global mean
     (exact-average theorem, App. C.1); distortion follows M^-k - M^-d."""
