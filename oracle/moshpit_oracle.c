@@ -286,6 +286,56 @@ int oracle_schedule_masks(int32_t kind, double p, uint64_t seed, int32_t down,
     return 0;
 }
 
+/* ---- a returning peer first takes the parameters of an up-to-date peer ---- */
+
+/*
+ * App. "Training with a dynamic number of peers": a participant that joins (or
+ * comes back desynchronised) downloads the latest parameters from a random
+ * up-to-date peer before it takes part again; otherwise its stale vector would
+ * undo progress of the others.  The paper fixes neither who counts as up to
+ * date nor the draw.  Taken here: peer i returns in round t when it is present
+ * in round t and was absent in round t-1; the up-to-date peers it can reach
+ * are those present in both rounds; the donor is the (u mod c)-th of these c
+ * candidates in ascending index, with
+ *   u(seed,t,i) = mix( mix(seed + 0xA0761D6478BD642F*(t+1)) ^ i )
+ * (the generator of the failure schedule on a stream of its own).  With no
+ * candidate nobody refreshes.  donor[i] = -1 for every peer that does not
+ * return.  Donors never return themselves, so the copies of oracle_refresh do
+ * not depend on their order.
+ */
+int oracle_refresh_donors(int64_t N, const uint8_t *prev, const uint8_t *cur, uint64_t seed, int64_t t,
+                          int32_t *donor)
+{
+    if (N < 0 || t < 0 || !prev || !cur || !donor) return -1;
+    int64_t c = 0;
+    for (int64_t j = 0; j < N; ++j)
+        if (prev[j] && cur[j]) ++c;
+    for (int64_t i = 0; i < N; ++i) {
+        donor[i] = -1;
+        if (!(cur[i] && !prev[i]) || c == 0) continue;
+        uint64_t u = mix64(mix64(seed + 0xA0761D6478BD642Full * (uint64_t)(t + 1)) ^ (uint64_t)i);
+        int64_t want = (int64_t)(u % (uint64_t)c);
+        for (int64_t j = 0; j < N; ++j) {
+            if (!(prev[j] && cur[j])) continue;
+            if (want == 0) { donor[i] = (int32_t)j; break; }
+            --want;
+        }
+    }
+    return 0;
+}
+
+/* X[i] <- X[donor[i]] for every i with donor[i] >= 0. */
+int oracle_refresh(double *X, int64_t N, int64_t W, int64_t ld, const int32_t *donor)
+{
+    if (!X || !donor || ld < W) return -1;
+    for (int64_t i = 0; i < N; ++i) {
+        if (donor[i] < 0) continue;
+        if (donor[i] >= N || donor[donor[i]] >= 0) return -1;      /* a donor must not be refreshing */
+        for (int64_t c = 0; c < W; ++c) X[i * ld + c] = X[(int64_t)donor[i] * ld + c];
+    }
+    return 0;
+}
+
 /* ---- failure during the all-reduce: the whole group skips ---------------- */
 
 /*

@@ -59,6 +59,8 @@ def _load():
         lib.oracle_local_step.argtypes = [_ptr, _ptr, _i64, _i64, _i64, _i64, _f64, _ptr]
         lib.oracle_sgd_round.argtypes = [_ptr, _ptr, _i64, _i64, _i64, _i64, _f64, _i32, _i32, _i64, _ptr]
         lib.oracle_skip_filter.argtypes = [_i64, _i32, _i32, _i64, _ptr, _ptr]
+        lib.oracle_refresh_donors.argtypes = [_i64, _ptr, _ptr, _u64, _i64, _ptr]
+        lib.oracle_refresh.argtypes = [_ptr, _i64, _i64, _i64, _ptr]
         lib.oracle_random_permutation.argtypes = [_u64, _i64, _i64, _ptr]
         lib.oracle_grouped_round.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _i64, _i32, _ptr]
         lib.oracle_random_groups_round.argtypes = [_ptr, _i64, _i64, _i64, _u64, _i64, _i32, _ptr]
@@ -184,6 +186,29 @@ def skip_filter(N: int, M: int, d: int, t: int, alive) -> np.ndarray:
     out = np.empty(N, dtype=np.uint8)
     _check(_load().oracle_skip_filter(N, M, d, t, a.ctypes.data, out.ctypes.data), "skip_filter")
     return out
+
+
+def refresh_donors(prev, cur, seed: int, t: int) -> np.ndarray:
+    """donor[i] >= 0 for every peer that returns in round t (present now, absent in round t-1):
+    the up-to-date peer whose parameters it takes; -1 elsewhere."""
+    a = np.ascontiguousarray(prev, dtype=np.uint8)
+    b = np.ascontiguousarray(cur, dtype=np.uint8)
+    if a.shape != b.shape or a.ndim != 1:
+        raise ValueError("masks must be two vectors of the same length")
+    donor = np.empty(a.shape[0], dtype=np.int32)
+    _check(_load().oracle_refresh_donors(a.shape[0], a.ctypes.data, b.ctypes.data, seed, t, donor.ctypes.data),
+           "refresh_donors")
+    return donor
+
+
+def refresh(X: np.ndarray, donor) -> None:
+    """X[i] <- X[donor[i]] wherever donor[i] >= 0."""
+    X = _state(X)
+    N, W = X.shape
+    dn = np.ascontiguousarray(donor, dtype=np.int32)
+    if dn.shape != (N,):
+        raise ValueError("donor must have shape (N,)")
+    _check(_load().oracle_refresh(X.ctypes.data, N, W, X.strides[0] // 8, dn.ctypes.data), "refresh")
 
 
 def random_permutation(seed: int, t: int, N: int) -> np.ndarray:

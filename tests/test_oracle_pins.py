@@ -535,6 +535,122 @@ def test_skip_semantics_properties():
 
 
 # --------------------------------------------------------------------------
+# a returning peer takes the parameters of an up-to-date peer first
+# (App. "Training with a dynamic number of peers")
+# --------------------------------------------------------------------------
+
+def test_refresh_hand_case():
+    """Four peers; peer 1 was away and comes back, peer 3 leaves.  The only peers
+    present in both rounds are 0 and 2, so peer 1 ends with the vector of one of
+    them and nothing else moves."""
+    prev = np.array([1, 0, 1, 1], dtype=np.uint8)
+    cur = np.array([1, 1, 1, 0], dtype=np.uint8)
+    X0 = np.array([[1.0, 10.0], [2.0, 20.0], [3.0, 30.0], [4.0, 40.0]])
+    seen = set()
+    for seed in range(40):
+        donor = orc.refresh_donors(prev, cur, seed, 5)
+        assert donor[0] == donor[2] == donor[3] == -1
+        assert donor[1] in (0, 2)
+        seen.add(int(donor[1]))
+        X = X0.copy()
+        orc.refresh(X, donor)
+        assert np.array_equal(X[1], X0[donor[1]])
+        assert np.array_equal(X[[0, 2, 3]], X0[[0, 2, 3]])
+    assert seen == {0, 2}                       # both candidates are drawn
+    # nobody present in both rounds: nobody to copy from
+    assert (orc.refresh_donors(np.array([0, 0, 1], dtype=np.uint8), np.array([1, 1, 0], dtype=np.uint8), 1, 0) == -1).all()
+    # nobody returns
+    assert (orc.refresh_donors(cur, cur, 1, 0) == -1).all()
+
+
+def test_refresh_donor_draw_matches_python_bigint_and_is_uniform():
+    """The draw against Python integers (64-bit wrap-around, stream constant, the
+    rank-th candidate in ascending order), then its statistics: donors are always
+    peers present in both rounds, never returning peers, and uniform over the
+    candidates."""
+    rng = np.random.default_rng(8)
+    N = 300
+    prev = (rng.random(N) < 0.7).astype(np.uint8)
+    cur = (rng.random(N) < 0.7).astype(np.uint8)
+    cand = [j for j in range(N) if prev[j] and cur[j]]
+    for t in (0, 3, 1000):
+        donor = orc.refresh_donors(prev, cur, 99, t)
+        for i in range(N):
+            if cur[i] and not prev[i]:
+                u = py_mix(py_mix((99 + 0xA0761D6478BD642F * (t + 1)) & MASK64) ^ i)
+                assert donor[i] == cand[u % len(cand)]
+            else:
+                assert donor[i] == -1
+    # uniformity: 20 candidates, many returning peers and rounds
+    N = 4000
+    prev = np.zeros(N, dtype=np.uint8); prev[:20] = 1
+    cur = np.ones(N, dtype=np.uint8)
+    counts = np.zeros(20)
+    for t in range(5):
+        donor = orc.refresh_donors(prev, cur, 7, t)
+        assert (donor[:20] == -1).all() and donor[20:].min() >= 0 and donor[20:].max() < 20
+        counts += np.bincount(donor[20:], minlength=20)
+    n = counts.sum()
+    chi2 = ((counts - n / 20) ** 2 / (n / 20)).sum()
+    assert chi2 < 50.0                           # 19 degrees of freedom: P(chi2 > 50) ~ 1e-4
+    # different rounds give different draws
+    assert not np.array_equal(orc.refresh_donors(prev, cur, 7, 0), orc.refresh_donors(prev, cur, 7, 1))
+
+
+def test_refresh_effect_on_a_run():
+    """What the step is for.  (a) Once the up-to-date peers agree, a returning peer
+    that refreshes agrees with them at once, while one that does not drags the swarm
+    back: the paper's reason for the step.  (b) Refreshing breaks the conservation of
+    the global sum by exactly the sum of (donor - stale) over the returning peers.
+    (c) On a die-and-rejoin schedule the distortion over the peers present at the end
+    is smaller with the step than without."""
+    rng = np.random.default_rng(31)
+    M, d, N, W = 4, 2, 16, 5
+    # (a) everybody but peer 5 averages to consensus; peer 5 was away the whole time
+    X = rng.normal(size=(N, W))
+    away = np.ones(N, dtype=np.uint8); away[5] = 0
+    T = 80                                      # with a peer missing the rest converge geometrically
+    for t in range(T):
+        orc.round_(X, M, d, t, away)
+    consensus = X[0].copy()
+    assert np.allclose(X[away == 1], consensus, atol=1e-13, rtol=0)
+    assert not np.allclose(X[5], consensus, atol=1e-3)
+    back = np.ones(N, dtype=np.uint8)
+    A, B = X.copy(), X.copy()
+    donor = orc.refresh_donors(away, back, 3, T)
+    assert donor[5] >= 0 and (np.delete(donor, 5) == -1).all()
+    orc.refresh(A, donor)
+    assert np.allclose(A, consensus, atol=1e-13, rtol=0)          # with the step: consensus kept
+    orc.round_(A, M, d, T, back)
+    orc.round_(B, M, d, T, back)                                   # without: the stale vector leaks in
+    assert orc.dist_to_mean(A) < 1e-24 < 1e-6 < orc.dist_to_mean(B)
+    # (b)
+    X = rng.normal(size=(N, W))
+    prev = (rng.random(N) < 0.6).astype(np.uint8)
+    cur = (rng.random(N) < 0.8).astype(np.uint8)
+    donor = orc.refresh_donors(prev, cur, 11, 4)
+    Y = X.copy()
+    orc.refresh(Y, donor)
+    ret = np.flatnonzero(donor >= 0)
+    assert len(ret) > 0
+    assert np.allclose(Y.sum(axis=0) - X.sum(axis=0), (X[donor[ret]] - X[ret]).sum(axis=0), atol=1e-12, rtol=0)
+    # (c)
+    M, d, N = 8, 2, 64
+    gain = []
+    for seed in range(12):
+        X0 = rng.normal(size=(N, 8)) + rng.normal(size=(N, 1))
+        masks = orc.schedule_masks(2, 0.15, 100 + seed, 2, N, 0, 10)
+        A, B = X0.copy(), X0.copy()
+        for t in range(10):
+            if t > 0:
+                orc.refresh(A, orc.refresh_donors(masks[t - 1], masks[t], seed, t))
+            orc.round_(A, M, d, t, masks[t])
+            orc.round_(B, M, d, t, masks[t])
+        gain.append(orc.dist_to_mean_subset(B, masks[-1]) / orc.dist_to_mean_subset(A, masks[-1]))
+    assert np.median(gain) > 2.0 and min(gain) > 0.8
+
+
+# --------------------------------------------------------------------------
 # averaging in random groups: the exact contraction rate of Thm 3.2
 # --------------------------------------------------------------------------
 
