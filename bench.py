@@ -241,6 +241,29 @@ def main() -> int:
         log(f"[bench] Moshpit SGD round: {sg_ms:.3f} ms per round, {sgd['gbps']} GB/s")
         del G
 
+    # returning peers copy an up-to-date peer's parameters (App. on a dynamic number of peers):
+    # 2*s*P bytes per returning peer; masks of consecutive rounds of the workload's schedule
+    refresh = None
+    if not args.no_fused and all_masks.shape[0] >= 2:
+        stream = torch.cuda.current_stream(dev)
+        pairs = [(all_masks[r - 1], all_masks[r]) for r in range(1, min(all_masks.shape[0], 1 + w.rounds))]
+        returning = sum(int(((b == 1) & (a == 0)).sum()) for a, b in pairs if int(((a == 1) & (b == 1)).sum()) > 0)
+        if returning > 0:
+            m.refresh(1, 88, pairs[0][0], pairs[0][1])
+            m.sync()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for r, (a, b) in enumerate(pairs):
+                m.refresh(1 + r, 88, a, b)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            rf_ms = e0.elapsed_time(e1) / len(pairs)
+            rf_bytes = 2.0 * s * w.P * returning / len(pairs)
+            refresh = {"ms_per_refresh": round(rf_ms, 4), "returning_peers": round(returning / len(pairs), 1),
+                       "gbps": round(rf_bytes / (rf_ms * 1e-3) / 1e9, 1),
+                       "note": "donor draw + row copies; includes the host-to-device copy of the two masks"}
+            log(f"[bench] refresh of returning peers: {rf_ms:.3f} ms, {refresh['gbps']} GB/s")
+
     copy_gbps = None
     if not args.no_copy_probe:
         nbytes = min(w.N * w.P * s, 8 * 2 ** 30)
@@ -316,6 +339,7 @@ def main() -> int:
         "random_groups": random_groups,
         "dynamic_keys": dynamic,
         "sgd_round": sgd,
+        "refresh": refresh,
         "cpu_baseline": cpu,
     }
     m.close()

@@ -80,6 +80,11 @@ typedef struct {
                                        member sits the round out (Sec. 3.1: a
                                        failure during the all-reduce makes the
                                        groupmates skip the round)               */
+    int32_t  refresh;               /* 1: before every round of a run but its
+                                       first, a peer that returns takes the
+                                       parameters of an up-to-date peer (see
+                                       moshpit_refresh), drawn with `seed`; such
+                                       a run is never fused                      */
 } moshpit_schedule;
 
 /* Flags of moshpit_run.
@@ -206,6 +211,26 @@ int moshpit_sgd_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host, cons
 int moshpit_random_groups_round(moshpit_ctx *h, int64_t t, uint64_t seed, int32_t group_size,
                                 const uint8_t *alive_host);
 int moshpit_random_permutation(moshpit_ctx *h, int64_t t, uint64_t seed, int32_t *perm_host);
+
+/* A returning peer takes the parameters of an up-to-date peer before it takes
+ * part again (App. "Training with a dynamic number of peers": a participant that
+ * joins or has fallen behind downloads the latest parameters from a random
+ * up-to-date peer, so that its stale vector does not undo the others' progress).
+ * The paper fixes neither who is up to date nor the draw; here: peer i returns
+ * in round t when alive_cur[i] != 0 and alive_prev[i] == 0 (the masks of rounds t
+ * and t-1); the candidates are the c peers present in both rounds; the donor of
+ * i is the (u mod c)-th candidate in ascending index,
+ *   u = mix(mix(seed + 0xA0761D6478BD642F*(t+1)) ^ i)   (mix as for the schedule);
+ * with c = 0 nothing happens.  moshpit_refresh copies row donor(i) of the state
+ * onto row i for every returning peer (2*elem_size*P bytes each; queued on the
+ * bound stream, masks are host pointers of N bytes, copied before return).  Call
+ * it before the round t it prepares.  The global mean is NOT conserved by this
+ * step.  moshpit_refresh_donors only returns the draw (host, N int32, -1 for
+ * peers that do not return), computed by the same device kernel; waits. */
+int moshpit_refresh(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *alive_prev_host,
+                    const uint8_t *alive_cur_host);
+int moshpit_refresh_donors(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *alive_prev_host,
+                           const uint8_t *alive_cur_host, int32_t *donors_host);
 
 /* One round over caller-defined groups: consecutive chunks of group_size entries
  * of the peer list index_host[0..n_index) (host; distinct peers in [0, N);

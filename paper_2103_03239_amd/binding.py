@@ -23,7 +23,7 @@ RUN_DEFAULT, RUN_FUSED = 0, 1
 EXPORTS = [
     "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",
     "moshpit_run", "moshpit_dist_to_mean", "moshpit_dist_to_mean_subset", "moshpit_group_keys", "moshpit_schedule_mask",
-    "moshpit_dynamic_reset", "moshpit_dynamic_round", "moshpit_dynamic_keys", "moshpit_local_step", "moshpit_sgd_round", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
+    "moshpit_dynamic_reset", "moshpit_dynamic_round", "moshpit_dynamic_keys", "moshpit_local_step", "moshpit_sgd_round", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_refresh", "moshpit_refresh_donors", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
 ]
 
 
@@ -33,7 +33,8 @@ class MoshpitError(RuntimeError):
 
 class _CSchedule(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("down_rounds", ctypes.c_int32), ("p", ctypes.c_double),
-                ("seed", ctypes.c_uint64), ("explicit_masks", ctypes.c_void_p), ("group_skip", ctypes.c_int32)]
+                ("seed", ctypes.c_uint64), ("explicit_masks", ctypes.c_void_p), ("group_skip", ctypes.c_int32),
+                ("refresh", ctypes.c_int32)]
 
 
 @dataclass
@@ -44,6 +45,7 @@ class Schedule:
     down_rounds: int = 0
     explicit_masks: np.ndarray | None = None      # uint8 [rounds, N] for SCHED_EXPLICIT
     group_skip: bool = False                      # a group with an absent member skips the round
+    refresh: bool = False                         # a returning peer first copies an up-to-date peer
 
 
 _lib = None
@@ -75,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_sgd_round.argtypes = [vp, i64, vp, vp, i64, ctypes.c_float]
     lib.moshpit_random_groups_round.argtypes = [vp, i64, ctypes.c_uint64, i32, vp]
     lib.moshpit_random_permutation.argtypes = [vp, i64, ctypes.c_uint64, vp]
+    lib.moshpit_refresh.argtypes = [vp, i64, ctypes.c_uint64, vp, vp]
+    lib.moshpit_refresh_donors.argtypes = [vp, i64, ctypes.c_uint64, vp, vp, vp]
     lib.moshpit_grouped_round.argtypes = [vp, vp, i64, i32, vp]
     lib.moshpit_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.moshpit_copy_probe.argtypes = [vp, vp, i64, vp]
@@ -98,7 +102,7 @@ def _c_schedule(s: Schedule | None, rounds: int, N: int):
         if keep.shape != (rounds, N):
             raise ValueError("explicit masks must have shape (rounds, N)")
         ptr = keep.ctypes.data
-    return _CSchedule(s.kind, s.down_rounds, float(s.p), s.seed, ptr, 1 if s.group_skip else 0), keep
+    return _CSchedule(s.kind, s.down_rounds, float(s.p), s.seed, ptr, 1 if s.group_skip else 0, 1 if s.refresh else 0), keep
 
 
 class Moshpit:
@@ -259,6 +263,24 @@ class Moshpit:
         perm = np.empty(self.N, dtype=np.int32)
         self._check(self._lib.moshpit_random_permutation(self._h, t, seed, perm.ctypes.data), "random_permutation")
         return perm
+
+    def _two_masks(self, prev, cur):
+        a = np.ascontiguousarray(prev, dtype=np.uint8)
+        b = np.ascontiguousarray(cur, dtype=np.uint8)
+        if a.shape != (self.N,) or b.shape != (self.N,):
+            raise ValueError("masks must have shape (N,)")
+        return a, b
+
+    def refresh(self, t: int, seed: int, alive_prev, alive_cur) -> None:
+        a, b = self._two_masks(alive_prev, alive_cur)
+        self._check(self._lib.moshpit_refresh(self._h, t, seed, a.ctypes.data, b.ctypes.data), "refresh")
+
+    def refresh_donors(self, t: int, seed: int, alive_prev, alive_cur) -> np.ndarray:
+        a, b = self._two_masks(alive_prev, alive_cur)
+        donors = np.empty(self.N, dtype=np.int32)
+        self._check(self._lib.moshpit_refresh_donors(self._h, t, seed, a.ctypes.data, b.ctypes.data,
+                                                     donors.ctypes.data), "refresh_donors")
+        return donors
 
     def grouped_round(self, index, group_size: int, alive=None) -> None:
         idx = np.ascontiguousarray(index, dtype=np.int32)

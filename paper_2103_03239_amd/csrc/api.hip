@@ -27,6 +27,10 @@ struct moshpit_ctx {
     int32_t *d_dyn = nullptr;          // chunk-index keys and their scratch (see dyn_layout)
     uint8_t *d_masks = nullptr;        // mask_rounds_cap * N bytes, for runs
     int64_t mask_rounds_cap = 0;
+    uint8_t *d_masks_raw = nullptr;    // raw_rounds_cap * N bytes: presence before the group-skip filter
+    int64_t raw_rounds_cap = 0;
+    int32_t *d_refresh = nullptr;      // 3 N + 2 int32: candidates, donors, returning peers, counts
+    uint8_t *d_refresh_masks = nullptr;  // 2 N bytes, for moshpit_refresh(host masks)
     int32_t *d_keys = nullptr;         // N
     double *d_partials = nullptr;      // partials_cap doubles
     int64_t partials_cap = 0;
@@ -143,8 +147,57 @@ int queue_masks(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t r
         HIP_TRY(h, launch_schedule(kind, threshold, s ? s->seed : 0, s ? s->down_rounds : 0, h->N, t0, rounds,
                                    h->d_masks, h->stream));
     }
-    if (s && s->group_skip)
+    if (s && s->group_skip) {
+        if (s->refresh) {
+            // who returns is a matter of presence, not of which groups skipped
+            if (rounds > h->raw_rounds_cap) {
+                if (h->d_masks_raw) {
+                    HIP_TRY(h, hipStreamSynchronize(h->stream));
+                    HIP_TRY(h, hipFree(h->d_masks_raw));
+                    h->d_masks_raw = nullptr;
+                    h->raw_rounds_cap = 0;
+                }
+                HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_masks_raw), static_cast<size_t>(rounds * h->N)));
+                h->raw_rounds_cap = rounds;
+            }
+            HIP_TRY(h, hipMemcpyAsync(h->d_masks_raw, h->d_masks, static_cast<size_t>(rounds) * h->N,
+                                      hipMemcpyDeviceToDevice, h->stream));
+        }
         HIP_TRY(h, launch_skip_filter(h->d_masks, h->N, h->M, h->d, t0, rounds, h->stream));
+    }
+    return MOSHPIT_OK;
+}
+
+int reserve_refresh(moshpit_ctx *h)
+{
+    if (h->d_refresh) return MOSHPIT_OK;
+    HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_refresh), sizeof(int32_t) * (3 * static_cast<size_t>(h->N) + 2)));
+    return MOSHPIT_OK;
+}
+
+// Draw the donors of round t from two device masks and, if asked, copy their rows.
+int queue_refresh(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *prev_dev, const uint8_t *cur_dev,
+                  bool copy)
+{
+    int rc = reserve_refresh(h);
+    if (rc != MOSHPIT_OK) return rc;
+    int32_t *candidates = h->d_refresh, *donor = candidates + h->N, *returning = donor + h->N;
+    int32_t *counts = returning + h->N;
+    HIP_TRY(h, launch_refresh_plan(prev_dev, cur_dev, h->N, seed, t, candidates, donor, returning, counts, h->stream));
+    if (copy)
+        HIP_TRY(h, launch_refresh_copy(h->X, h->dtype, h->N, h->P, h->row_stride, donor, returning, counts, h->stream));
+    return MOSHPIT_OK;
+}
+
+int stage_refresh_masks(moshpit_ctx *h, const uint8_t *prev_host, const uint8_t *cur_host)
+{
+    if (!prev_host || !cur_host) return fail(h, MOSHPIT_EINVAL, "both masks are required");
+    if (h->N > 0x7fffffffLL) return fail(h, MOSHPIT_EINVAL, "too many peers for 32-bit donor indices");
+    if (!h->d_refresh_masks)
+        HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_refresh_masks), 2 * static_cast<size_t>(h->N)));
+    HIP_TRY(h, hipMemcpyAsync(h->d_refresh_masks, prev_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, hipMemcpyAsync(h->d_refresh_masks + h->N, cur_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice,
+                              h->stream));
     return MOSHPIT_OK;
 }
 
@@ -209,6 +262,9 @@ int moshpit_destroy(moshpit_ctx *h)
     if (h->d_perm) (void)hipFree(h->d_perm);
     if (h->d_dyn) (void)hipFree(h->d_dyn);
     if (h->d_masks) (void)hipFree(h->d_masks);
+    if (h->d_masks_raw) (void)hipFree(h->d_masks_raw);
+    if (h->d_refresh) (void)hipFree(h->d_refresh);
+    if (h->d_refresh_masks) (void)hipFree(h->d_refresh_masks);
     if (h->d_keys) (void)hipFree(h->d_keys);
     if (h->d_partials) (void)hipFree(h->d_partials);
     if (h->d_dist) (void)hipFree(h->d_dist);
@@ -276,8 +332,11 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
     if (flags & ~MOSHPIT_RUN_FUSED) return fail(h, MOSHPIT_EINVAL, "unknown flags 0x%x", flags);
     rc = check_schedule(h, s, t0, rounds);
     if (rc != MOSHPIT_OK) return rc;
-    const bool fused = (flags & MOSHPIT_RUN_FUSED) != 0;
     const bool failures = s && s->kind != MOSHPIT_SCHED_NONE;
+    const bool refresh = failures && s->refresh != 0;
+    if (refresh && h->N > 0x7fffffffLL) return fail(h, MOSHPIT_EINVAL, "too many peers for 32-bit donor indices");
+    // a refresh between two rounds moves rows across tiles: such runs go round by round
+    const bool fused = (flags & MOSHPIT_RUN_FUSED) != 0 && !refresh;
     if (failures) {
         rc = queue_masks(h, s, t0, rounds);
         if (rc != MOSHPIT_OK) return rc;
@@ -303,6 +362,12 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
         FusedPlan plan;
         const bool fuse = fused && plan_fused(h->dtype, h->N, h->M, h->d, h->P, h->row_stride, h->X, t0 + r,
                                               rounds - r, &plan);
+        if (refresh && r > 0) {
+            const uint8_t *presence = s->group_skip ? h->d_masks_raw : h->d_masks;
+            rc = queue_refresh(h, t0 + r, s->seed, presence + static_cast<int64_t>(r - 1) * h->N,
+                               presence + static_cast<int64_t>(r) * h->N, true);
+            if (rc != MOSHPIT_OK) return rc;
+        }
         if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * pass], h->stream));
         int32_t done = 1;
         if (fuse) {
@@ -550,6 +615,33 @@ int moshpit_random_groups_round(moshpit_ctx *h, int64_t t, uint64_t seed, int32_
     if (!h->d_perm) HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_perm), sizeof(int32_t) * static_cast<size_t>(h->N)));
     HIP_TRY(h, launch_random_permutation(seed, t, h->N, h->d_perm, h->stream));
     return queue_list_round(h, h->d_perm, h->N, group_size, alive_host);
+}
+
+int moshpit_refresh(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *alive_prev_host,
+                    const uint8_t *alive_cur_host)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
+    rc = stage_refresh_masks(h, alive_prev_host, alive_cur_host);
+    if (rc != MOSHPIT_OK) return rc;
+    return queue_refresh(h, t, seed, h->d_refresh_masks, h->d_refresh_masks + h->N, true);
+}
+
+int moshpit_refresh_donors(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *alive_prev_host,
+                           const uint8_t *alive_cur_host, int32_t *donors_host)
+{
+    if (!h) return MOSHPIT_EINVAL;
+    if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
+    if (!donors_host) return fail(h, MOSHPIT_EINVAL, "donors is NULL");
+    int rc = stage_refresh_masks(h, alive_prev_host, alive_cur_host);
+    if (rc != MOSHPIT_OK) return rc;
+    rc = queue_refresh(h, t, seed, h->d_refresh_masks, h->d_refresh_masks + h->N, false);
+    if (rc != MOSHPIT_OK) return rc;
+    HIP_TRY(h, hipMemcpyAsync(donors_host, h->d_refresh + h->N, sizeof(int32_t) * static_cast<size_t>(h->N),
+                              hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return MOSHPIT_OK;
 }
 
 int moshpit_grouped_round(moshpit_ctx *h, const int32_t *index_host, int64_t n_index, int32_t group_size,

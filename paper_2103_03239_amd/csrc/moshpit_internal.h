@@ -3,6 +3,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 #include <stdint.h>
 
 namespace moshpit {
@@ -73,6 +75,16 @@ hipError_t launch_dynamic_grouping(int64_t N, int32_t M, int32_t d, uint64_t see
 // Queue the group-skip filter on masks[rounds][N] (device, in place) for rounds t0..
 hipError_t launch_skip_filter(uint8_t *masks, int64_t N, int32_t M, int32_t d, int64_t t0, int rounds,
                               hipStream_t stream);
+
+// Returning peers (present in `cur`, absent in `prev`; device masks of N bytes): draw
+// their donors among the peers present in both, list them, then copy the donors' rows.
+// candidates, donor, returning: device, N int32 each; counts: device, 2 int32
+// (candidates, returning peers).  The copy reads donor/returning/counts on the device.
+hipError_t launch_refresh_plan(const uint8_t *prev, const uint8_t *cur, int64_t N, uint64_t seed, int64_t t,
+                               int32_t *candidates, int32_t *donor, int32_t *returning, int32_t *counts,
+                               hipStream_t stream);
+hipError_t launch_refresh_copy(void *X, int dtype, int64_t N, int64_t P, int64_t row_stride, const int32_t *donor,
+                               const int32_t *returning, const int32_t *counts, hipStream_t stream);
 
 // Queue the random-permutation kernel: perm[r] = peer of rank r when the peers
 // are ordered by their 64-bit key of (seed, t), ties by index (device, N int32).

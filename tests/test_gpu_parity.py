@@ -540,6 +540,120 @@ def test_group_skip_schedule(M, d, P, dtype, p, fused):
 
 
 # --------------------------------------------------------------------------
+# a returning peer copies an up-to-date peer (App. on a dynamic number of peers)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,d", [(4, 2), (7, 2), (16, 2), (32, 2), (16, 3), (2, 11), (64, 1)])
+def test_refresh_donors_bit_exact(M, d):
+    """The draw of the donors against the oracle's, byte for byte, over random and
+    degenerate pairs of masks (more peers than one pass of the planning block,
+    nobody to copy from, nobody returning, everybody returning)."""
+    N = M ** d
+    say(f"refresh donors N={N}")
+    rng = np.random.default_rng(N)
+    X = torch.zeros(N, 8, device=DEV)
+    ones, zeros = np.ones(N, dtype=np.uint8), np.zeros(N, dtype=np.uint8)
+    one_left = zeros.copy(); one_left[N // 2] = 1
+    cases = [((rng.random(N) < a).astype(np.uint8), (rng.random(N) < b).astype(np.uint8))
+             for a, b in ((0.5, 0.5), (0.9, 0.8), (0.1, 0.9), (0.02, 0.98))]
+    cases += [(zeros, ones), (ones, ones), (ones, zeros), (one_left, ones), (zeros, zeros)]
+    with binding.Moshpit(N, 8, M, d, 0) as m:
+        m.bind_state(X)
+        for k, (prev, cur) in enumerate(cases):
+            for t, seed in ((0, 1), (5, 2**63 + 11), (10**6, 77)):
+                got = m.refresh_donors(t, seed, prev, cur)
+                assert np.array_equal(got, orc.refresh_donors(prev, cur, seed, t)), f"case {k} t={t}"
+
+
+@pytest.mark.parametrize("M,d,P,dtype,pad,offset", [(16, 2, 40_000, 0, 0, 0), (4, 3, 9_999, 0, 1, 0), (8, 2, 8_195, 1, 5, 0),
+                                                     (32, 2, 3_001, 0, 3, 1), (7, 2, 20_001, 1, 7, 3), (5, 2, 1, 0, 0, 0)])
+def test_refresh_copies_rows_exactly(M, d, P, dtype, pad, offset):
+    """moshpit_refresh: returning rows become bit copies of their donors' rows, nothing
+    else changes (other rows, padding, guard elements) - aligned rows take the 128-bit
+    path with an element-wise ragged end, unaligned ones the element-wise path."""
+    N = M ** d
+    stride = P + pad
+    w = inputs.Workload("refresh", N, M, d, P, dtype, "normal", 0, 0.0, 0, 0, 5 + P, 6)
+    say(f"refresh copy {w} stride={stride} offset={offset}")
+    buf = torch.full((N * stride + offset + 64,), 512.0, dtype=w.torch_dtype, device=DEV)
+    X = buf[offset: offset + N * stride].view(N, stride)[:, :P]
+    X.copy_(inputs.make_state(w, DEV))
+    before = buf.clone()
+    rng = np.random.default_rng(P)
+    prev = (rng.random(N) < 0.6).astype(np.uint8)
+    cur = (rng.random(N) < 0.8).astype(np.uint8)
+    donor = orc.refresh_donors(prev, cur, 9, 4)
+    assert (donor >= 0).any()
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(X)
+        m.refresh(4, 9, prev, cur)
+        m.sync()
+    want = before.clone()
+    Wv = want[offset: offset + N * stride].view(N, stride)
+    Bv = before[offset: offset + N * stride].view(N, stride)
+    idx = torch.from_numpy(np.flatnonzero(donor >= 0)).to(DEV)
+    src = torch.from_numpy(donor[donor >= 0].astype(np.int64)).to(DEV)
+    Wv[idx, :P] = Bv[src, :P]
+    assert torch.equal(buf, want)
+
+
+@pytest.mark.parametrize("M,d,P,dtype,kind,p,skip", [(16, 2, 3_000, 0, 2, 0.15, False), (4, 3, 1_001, 0, 1, 0.3, False),
+                                                      (16, 3, 264, 1, 2, 0.1, False), (8, 2, 2_048, 0, 2, 0.1, True),
+                                                      (32, 2, 520, 1, 1, 0.2, True)])
+def test_run_with_refresh(M, d, P, dtype, kind, p, skip):
+    """A run whose schedule asks for the refresh: before every round but the first the
+    returning peers copy their donors (drawn from the presence masks, also when the
+    group-skip filter then thins the participation), then the round runs.  Against the
+    oracle taking the same steps one by one; the run is not fused even when allowed."""
+    N, rounds, seed = M ** d, 9, 1234
+    w = inputs.Workload("run-refresh", N, M, d, P, dtype, "peer_offset", kind, p, 2, rounds, 71, seed)
+    say(f"run with refresh {w} skip={skip}")
+    X = inputs.make_state(w, DEV)
+    ref = to_f64(X).copy()
+    presence = orc.schedule_masks(kind, p, seed, 2, N, 0, rounds)
+    dist_ref = [orc.dist_to_mean(ref)]
+    n_copies = 0
+    for t in range(rounds):
+        if t > 0:
+            donor = orc.refresh_donors(presence[t - 1], presence[t], seed, t)
+            n_copies += int((donor >= 0).sum())
+            orc.refresh(ref, donor)
+        eff = orc.skip_filter(N, M, d, t, presence[t]) if skip else presence[t]
+        orc.round_(ref, M, d, t, eff)
+        dist_ref.append(orc.dist_to_mean(ref))
+    assert n_copies > 0
+    sched = binding.Schedule(kind=kind, p=p, seed=seed, down_rounds=2, group_skip=skip, refresh=True)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(X)
+        dist, _ = m.run(0, rounds, sched, want_dist=True, flags=binding.RUN_FUSED)
+    assert not np.isnan(dist).any(), "a run with refresh must go round by round"
+    assert_state_close(to_f64(X), ref, TOL[dtype], w.name)
+    assert_dist_close(dist, np.array(dist_ref), TOL[dtype], dist_floor(P, dtype, 1.0), w.name)
+
+
+def test_refresh_full_size_workload5():
+    """Workload 5 at full size (4096 peers that die and come back after 2 rounds): a run
+    with the refresh against the oracle on sampled columns."""
+    w = inputs.CONFIGS[5]
+    say(f"refresh full-size {w.name}")
+    X = inputs.make_state(w, DEV)
+    cols = sample_columns(w.P, 1024, seed=505)
+    tc = torch.from_numpy(cols).to(DEV)
+    ref = X[:, tc].to(torch.float64).cpu().numpy().copy()
+    presence = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, w.N, 0, w.rounds)
+    for t in range(w.rounds):
+        if t > 0:
+            orc.refresh(ref, orc.refresh_donors(presence[t - 1], presence[t], w.mask_seed, t))
+        orc.round_(ref, w.M, w.d, t, presence[t])
+    sched = binding.Schedule(kind=w.kind, p=w.p, seed=w.mask_seed, down_rounds=w.down, refresh=True)
+    with binding.Moshpit(w.N, w.P, w.M, w.d, w.dtype) as m:
+        m.bind_state(X)
+        m.run(0, w.rounds, sched)
+        m.sync()
+    assert_state_close(X[:, tc].to(torch.float64).cpu().numpy(), ref, TOL[w.dtype], w.name)
+
+
+# --------------------------------------------------------------------------
 # Moshpit SGD iterations (Alg. 2)
 # --------------------------------------------------------------------------
 
