@@ -63,22 +63,22 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// x + (x of the lane 16 / 32 lanes away, lane index xor 16 / 32), without a
-// trip through LDS: the swap instructions exchange rows of 16 (halves of 32)
-// lanes between their two operands, after which each operand holds one of the
-// two addends in every lane.  Addition commutes, so both partners get the same
-// bits.
-__device__ __forceinline__ float add_across_16(float x)
+// Lane exchanges without a trip through LDS.  With rows of 16 lanes r0..r3,
+//   swap16(a, b) = ([a.r0, b.r0, a.r2, b.r2], [a.r1, b.r1, a.r3, b.r3])
+//   swap32(a, b) = ([a.r0, a.r1, b.r0, b.r1], [a.r2, a.r3, b.r2, b.r3])
+// (v_permlane16_swap / v_permlane32_swap).  Adding the two results of a swap of
+// two DIFFERENT values reduces both across a pair of rows at once and leaves
+// one of them in each row of the pair: the transposing reduction used below.
+struct LanePair { float first, second; };
+__device__ __forceinline__ LanePair swap16(float a, float b)
 {
-    const uint32_t b = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane16_swap(b, b, false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return LanePair{__uint_as_float(r[0]), __uint_as_float(r[1])};
 }
-__device__ __forceinline__ float add_across_32(float x)
+__device__ __forceinline__ LanePair swap32(float a, float b)
 {
-    const uint32_t b = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return LanePair{__uint_as_float(r[0]), __uint_as_float(r[1])};
 }
 
 // CV consecutive columns of one row in LDS, widened to binary32.
@@ -409,12 +409,30 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
                             for (int u = 0; u + w2 < PER; u += 2 * w2)
 #pragma unroll
                                 for (int e = 0; e < CV; ++e) f[u][e] += f[u + w2][e];
-#pragma unroll
-                        for (int e = 0; e < CV; ++e) {
-                            float part = f[0][e];
-                            if constexpr (SPLIT > 2) part = add_across_16(part);      // sub ^ 1
-                            part = add_across_32(part);                               // sub ^ 1 (SPLIT 2) or sub ^ 2
-                            acc[e] += part;
+                        // The SPLIT lanes of an item hold partial sums of its 4 columns.  They
+                        // are added across lanes so that each lane ends with the total of ONE
+                        // column (same order as the full tree: (s0 + s1) + (s2 + s3)), divides
+                        // that one, and the quotients are handed round: 6 (4) exchanges and 1
+                        // (2) divisions per lane instead of 8 (4) exchanges and 4 divisions.
+                        static_assert(CV == 4, "lane-split items work on 4 columns");
+                        const float k = static_cast<float>(cnt);
+                        if constexpr (SPLIT == 4) {
+                            const LanePair a = swap16(f[0][0], f[0][1]);    // rows 0, 2: column 0; rows 1, 3: column 1
+                            const LanePair b = swap16(f[0][2], f[0][3]);    // rows 0, 2: column 2; rows 1, 3: column 3
+                            const LanePair c = swap32(a.first + a.second, b.first + b.second);
+                            const float mean = (0.f + (c.first + c.second)) / k;    // row r: column r
+                            const LanePair eo = swap16(mean, mean);         // columns 0|2 and 1|3 of my half
+                            const LanePair m02 = swap32(eo.first, eo.first);
+                            const LanePair m13 = swap32(eo.second, eo.second);
+                            acc[0] = m02.first; acc[1] = m13.first; acc[2] = m02.second; acc[3] = m13.second;
+                        } else {
+                            const LanePair a = swap32(f[0][0], f[0][1]);    // lower half: column 0, upper: column 1
+                            const LanePair b = swap32(f[0][2], f[0][3]);    // lower half: column 2, upper: column 3
+                            const float q01 = (0.f + (a.first + a.second)) / k;
+                            const float q23 = (0.f + (b.first + b.second)) / k;
+                            const LanePair m01 = swap32(q01, q01);
+                            const LanePair m23 = swap32(q23, q23);
+                            acc[0] = m01.first; acc[1] = m01.second; acc[2] = m23.first; acc[3] = m23.second;
                         }
                     } else if constexpr (TREE < 16) {
                         float t0[CV];
@@ -431,9 +449,11 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
                             for (int e = 0; e < CV; ++e) acc[e] += t16[e];
                         }
                     }
-                    const float k = static_cast<float>(cnt);
+                    if constexpr (SPLIT == 1) {
+                        const float k = static_cast<float>(cnt);
 #pragma unroll
-                    for (int e = 0; e < CV; ++e) acc[e] = acc[e] / k;
+                        for (int e = 0; e < CV; ++e) acc[e] = acc[e] / k;
+                    }
                     if constexpr (SPLIT > 1) {
 #pragma unroll
                         for (int u = 0; u < PER; ++u) Q::store(pos[u], acc);
