@@ -29,7 +29,8 @@
 //
 // LDS layout (dynamic): [tile: rows x Wb bytes][2 x bitmaps: rounds x groups
 // u64][byte offset of every local row][2 x row flags: rows bytes][tile offset of
-// the first row of every group per axis][pad][16 bytes of zeros][16 bytes of write-only trash].
+// the first row of every group per axis][pad][RN(1/k), k = 0..64][16 bytes of zeros][16 bytes
+// of write-only trash].
 #include "moshpit_internal.h"
 
 namespace moshpit {
@@ -43,6 +44,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // 160 / BPC KiB of LDS, so a compute unit always runs 16 waves on one or two tiles.
 constexpr int threads_of(int bpc) { return 1024 / bpc; }
 constexpr int lds_of(int bpc) { return 160 * 1024 / bpc; }
+constexpr int kRcpBytes = 272;       // 65 reciprocals, padded to a multiple of 16 bytes
+constexpr int kNormalOrZero = 0x168;  // v_cmp_class mask: -normal, -0, +0, +normal
 constexpr int kMinSeg = 128;          // fewest bytes of a row in a tile
 constexpr int kPrefetch = 8;          // 128-bit vectors per thread: 1024 * 8 * 16 B = 128 KiB of tile
 
@@ -245,6 +248,7 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
     int64_t *rowoff = reinterpret_cast<int64_t *>(bitmaps0 + 2 * bm_count);      // byte offset of local row lr
     uint8_t *rowflag0 = reinterpret_cast<uint8_t *>(rowoff + p.rows_padded);
     int32_t *lbase_tab = reinterpret_cast<int32_t *>(rowflag0 + 2 * p.rows_padded);
+    float *rcp_tab = reinterpret_cast<float *>(lds + p.lds_bytes - 32 - kRcpBytes);  // RN(1 / k), k = 0..64
     elem_t *zeros = reinterpret_cast<elem_t *>(lds + p.lds_bytes - 32);            // 16 bytes that hold 0
     elem_t *trash = reinterpret_cast<elem_t *>(lds + p.lds_bytes - 16);            // 16 bytes nobody reads
 
@@ -259,6 +263,7 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
     }
     for (int32_t lr = tid; lr < p.rows; lr += kThreads) rowoff[lr] = global_row(p, 0, lr) * p.row_bytes;
     if (tid < 4) reinterpret_cast<uint32_t *>(zeros)[tid] = 0u;
+    if (tid <= 64) rcp_tab[tid] = tid == 0 ? 0.f : 1.f / static_cast<float>(tid);
 
     const int32_t Wv = p.Wb / 16;
     const int32_t W = p.Wb / static_cast<int32_t>(sizeof(elem_t));     // columns of a full tile
@@ -373,9 +378,12 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
             int32_t gl = g_first, cc = c_first;
             while (gl < p.groups) {
                 const uint64_t live = bmr[gl];
-                const int32_t lbase = lb[gl];          // read together with the bitmap
+                int32_t lbase = lb[gl];
+                asm volatile("" : "+v"(lbase));        // keeps this read next to the bitmap's: one LDS latency, not two
                 const int cnt = __popcll(live);
                 if (cnt >= 2) {
+                    [[maybe_unused]] float y = 0.f;    // RN(1 / cnt), read along with the rows
+                    if constexpr (SPLIT == 1 && CV > 1) y = rcp_tab[cnt];
                     elem_t *col = reinterpret_cast<elem_t *>(tile + lbase) + cc * CV;
                     float acc[CV];
 #pragma unroll
@@ -449,10 +457,33 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
                             for (int e = 0; e < CV; ++e) acc[e] += t16[e];
                         }
                     }
-                    if constexpr (SPLIT == 1) {
+                    if constexpr (SPLIT == 1 && CV > 1) {
+                        // acc / k for CV columns, sharing the reciprocal y = RN(1/k) (a table in
+                        // LDS, filled by true divisions): q0 = RN(acc * y), the exact remainder
+                        // r = acc - k * q0 (one fma), q = RN(q0 + r * y) is the correctly rounded
+                        // quotient whenever nothing underflows.  A q that is not a normal number
+                        // or zero (NaN from an infinite sum, subnormal) is redone with a true
+                        // division.  With this guard the sequence was compared with the division
+                        // for every count k <= 64 and all 2^32 binary32 numerators: the only
+                        // difference is -0 / k, and acc is never -0 (it starts from +0).
                         const float k = static_cast<float>(cnt);
+                        float quo[CV];
+                        bool redo = false;
 #pragma unroll
-                        for (int e = 0; e < CV; ++e) acc[e] = acc[e] / k;
+                        for (int e = 0; e < CV; ++e) {
+                            const float q0 = __fmul_rn(acc[e], y);
+                            const float r = __fmaf_rn(-k, q0, acc[e]);
+                            quo[e] = __fmaf_rn(r, y, q0);
+                            redo = redo || !__builtin_amdgcn_classf(quo[e], kNormalOrZero);
+                        }
+                        if (redo) {
+#pragma unroll
+                            for (int e = 0; e < CV; ++e) quo[e] = acc[e] / k;
+                        }
+#pragma unroll
+                        for (int e = 0; e < CV; ++e) acc[e] = quo[e];
+                    } else if constexpr (SPLIT == 1) {
+                        acc[0] = acc[0] / static_cast<float>(cnt);
                     }
                     if constexpr (SPLIT > 1) {
 #pragma unroll
@@ -571,8 +602,9 @@ int tree_size(int32_t M) { return M > 8 ? 16 : M > 4 ? 8 : M > 2 ? 4 : 2; }
 int64_t fixed_lds(int64_t rounds, int64_t rows, int64_t groups, int64_t F)
 {
     const int64_t rows_padded = (rows + 15) / 16 * 16;
-    // tables, slack, then (16-byte aligned) 16 bytes of zeros and 16 bytes of write-only trash
-    return (2 * rounds * groups * 8 + rows_padded * 8 + 2 * rows_padded + F * groups * 4 + 32 + 15) / 16 * 16 + 32;
+    // tables, slack, then (16-byte aligned) the reciprocals, 16 bytes of zeros, 16 bytes of write-only trash
+    return (2 * rounds * groups * 8 + rows_padded * 8 + 2 * rows_padded + F * groups * 4 + 32 + 15) / 16 * 16 +
+           kRcpBytes + 32;
 }
 
 }  // namespace
