@@ -59,6 +59,14 @@ CONFIGS = {
 }
 
 
+def aligned_row_stride(P: int, dtype: int) -> int:
+    """Smallest row stride (in elements) >= P whose rows start on 128-byte boundaries, the
+    cache-line size of the GPU: measured worth about 5 % of HBM throughput on rows that
+    are not (25,557,032 binary32 parameters are 96 bytes short of one)."""
+    per_line = 128 // (4 if dtype == F32 else 2)
+    return -(-P // per_line) * per_line
+
+
 def make_state(w: Workload, device: str | torch.device = "cpu", row_stride: int | None = None) -> torch.Tensor:
     """Draw the [N, P] peer-state matrix of a workload in its storage dtype.
 
