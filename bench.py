@@ -331,6 +331,9 @@ def main() -> int:
         "group_mean_gbps": round(k1_gbps, 1),
         "group_mean_ms_per_round": round(k1_ms_per_launch, 4),
         "group_mean_rounds_per_s": round(1e3 / k1_ms_per_launch, 2),
+        "group_mean_ms_min_median_max": [round(float(round_ms.min()), 4), round(float(np.median(round_ms)), 4),
+                                         round(float(round_ms.max()), 4)],
+        "group_mean_pct_of_copy_probe": None if copy_gbps is None else round(100 * k1_gbps / copy_gbps, 1),
         **per_axis,
         "copy_probe_gbps": None if copy_gbps is None else round(copy_gbps, 1),
         "dist_to_mean_per_param": dists[-1] / w.P,

@@ -381,6 +381,63 @@ def test_fused_division_edge_values(M, d, dtype):
     assert bool(tiny.any()) and bool(torch.isinf(A).any() | torch.isnan(A).any())
 
 
+@pytest.mark.parametrize("fused", [0, 1])
+def test_run_can_be_continued(fused):
+    """A run split in two (the second part starting at the round where the first stopped) gives
+    the bits of the run in one piece, also when a peer's absence spans the cut (die-and-rejoin
+    schedule) and when the cut falls inside what would have been one fused pass."""
+    M, d, P, rounds, cut = 16, 2, 3_000, 9, 4
+    N = M ** d
+    w = inputs.Workload("continued", N, M, d, P, 0, "peer_offset", inputs.KIND_REJOIN, 0.15, 2, rounds, 81, 82)
+    say(f"continued run fused={fused}")
+    A = inputs.make_state(w, DEV)
+    B = A.clone()
+    flags = binding.RUN_FUSED if fused else 0
+    with binding.Moshpit(N, P, M, d, 0) as m:
+        m.bind_state(A)
+        da, _ = m.run(0, rounds, sched_of(w), want_dist=True, flags=flags)
+        m.bind_state(B)
+        d1, _ = m.run(0, cut, sched_of(w), want_dist=True, flags=flags)
+        d2, _ = m.run(cut, rounds - cut, sched_of(w), want_dist=True, flags=flags)
+        # zero rounds: nothing moves, one distortion value
+        before = B.clone()
+        d0, _ = m.run(rounds, 0, sched_of(w), want_dist=True, flags=flags)
+        m.sync()
+    assert torch.equal(A, B) and torch.equal(B, before)
+    assert d0.shape == (1,) and d0[0] == d2[-1] == da[-1]
+    assert d1[0] == da[0] and d1[-1] == d2[0]
+
+
+def test_fused_with_explicit_masks_and_dead_rounds():
+    """Explicit schedules through the fused path: a round in which nobody is present, a round
+    with one survivor per group and a peer absent throughout (its row is never touched)."""
+    M, d, P, rounds = 8, 2, 2_048, 6
+    N = M ** d
+    w = inputs.Workload("explicit", N, M, d, P, 0, "normal", 0, 0.0, 0, rounds, 91, 92)
+    say("fused explicit masks")
+    masks = orc.schedule_masks(1, 0.2, 92, 0, N, 0, rounds)
+    masks[2, :] = 0                                   # nobody
+    masks[3, :] = 0
+    masks[3, ::M] = 1                                 # round 3 averages along axis 1: peers 0, 8, ... share a group
+    masks[4, :] = 0
+    masks[4, :M] = 1                                  # round 4 (axis 0): one whole group, the rest absent
+    masks[:, 13] = 0                                  # peer 13 never takes part
+    A = inputs.make_state(w, DEV)
+    B = A.clone()
+    ref = to_f64(A).copy()
+    orc.run(ref, M, d, 0, rounds, masks)
+    sched = binding.Schedule(kind=binding.SCHED_EXPLICIT, explicit_masks=masks)
+    with binding.Moshpit(N, P, M, d, 0) as m:
+        m.bind_state(A)
+        m.run(0, rounds, sched)
+        m.bind_state(B)
+        dist, _ = m.run(0, rounds, sched, want_dist=True, flags=binding.RUN_FUSED)
+    assert np.isnan(dist[1:-1]).all(), "expected one fused pass"
+    assert torch.equal(A, B)
+    assert_state_close(to_f64(B), ref, TOL[0], w.name)
+    assert np.array_equal(to_f64(B)[13], to_f64(inputs.make_state(w, DEV))[13])
+
+
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
 def test_fused_full_size_matches_single_rounds(cfg):
     """Full-size workloads: the fused path reproduces the single-round path bit for bit."""
