@@ -47,3 +47,13 @@ def test_create_rejects_bad_shapes_without_a_gpu():
         assert lib.moshpit_last_error(None) != b""
     with pytest.raises(binding.MoshpitError):
         binding.Moshpit(15, 8, 4, 2, 0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU's share; asking for more ends with a message, not a run."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert out.returncode == 2
+    assert "ONE GPU" in out.stderr + out.stdout
