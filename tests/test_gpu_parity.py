@@ -438,6 +438,59 @@ def test_fused_with_explicit_masks_and_dead_rounds():
     assert np.array_equal(to_f64(B)[13], to_f64(inputs.make_state(w, DEV))[13])
 
 
+def _random_cases(count, seed):
+    """Seeded random shapes: grid, width, type, row padding, failure rate, first round, rounds."""
+    rng = np.random.default_rng(seed)
+    grids = [(2, 3), (2, 7), (3, 2), (3, 4), (4, 2), (4, 4), (5, 2), (5, 3), (6, 2), (8, 2), (8, 3), (9, 2), (11, 2),
+             (13, 2), (16, 2), (17, 2), (24, 2), (31, 2), (32, 2), (33, 2), (2, 12), (4, 5), (64, 1), (10, 1)]
+    cases = []
+    for k in range(count):
+        M, d = grids[int(rng.integers(len(grids)))]
+        dtype = int(rng.integers(2))
+        per16 = 4 if dtype == 0 else 8
+        P = int(rng.integers(1, 700))
+        if rng.random() < 0.7:
+            P = max(per16, P // per16 * per16)            # rows that the fused path accepts
+        pad = int(rng.choice([0, 0, per16, 3]))
+        p = float(rng.choice([0.0, 0.05, 0.3, 0.7]))
+        t0 = int(rng.integers(0, 7))
+        rounds = int(rng.integers(1, 3 * d + 3))
+        cases.append((M, d, P, dtype, pad, p, t0, rounds, 1000 + k))
+    return cases
+
+
+@pytest.mark.parametrize("M,d,P,dtype,pad,p,t0,rounds,seed", _random_cases(60, 2103))
+def test_random_shapes_single_and_fused(M, d, P, dtype, pad, p, t0, rounds, seed):
+    """Seeded random small shapes through both paths: the fused run gives the bits of the
+    round-by-round run, both agree with the oracle, padding stays untouched."""
+    N = M ** d
+    w = inputs.Workload(f"rand-{seed}", N, M, d, P, dtype, "peer_offset", inputs.KIND_IID if p > 0 else inputs.KIND_NONE,
+                        p, 0, rounds, seed, seed + 1)
+    say(f"case {w} pad={pad} t0={t0}")
+    stride = P + pad
+    bufA = torch.full((N * stride + 16,), 512.0, dtype=w.torch_dtype, device=DEV)
+    A = bufA[: N * stride].view(N, stride)[:, :P]
+    A.copy_(inputs.make_state(w, DEV))
+    bufB = bufA.clone()
+    B = bufB[: N * stride].view(N, stride)[:, :P]
+    ref = to_f64(A).copy()
+    masks = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, N, t0, rounds)
+    dist_ref = orc.run(ref, M, d, t0, rounds, masks, want_dist=True)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(A, )
+        dist_a, _ = m.run(t0, rounds, sched_of(w), want_dist=True)
+        m.bind_state(B)
+        dist_b, _ = m.run(t0, rounds, sched_of(w), want_dist=True, flags=binding.RUN_FUSED)
+    assert torch.equal(bufA, bufB), "fused run differs from single rounds (or padding was touched)"
+    assert_state_close(to_f64(A), ref, TOL[dtype], w.name)
+    have = ~np.isnan(dist_b)
+    assert np.array_equal(dist_b[have], dist_a[have])
+    assert_dist_close(dist_a, dist_ref, TOL[dtype], dist_floor(P, dtype, 1.5), w.name)
+    if pad:
+        whole = bufA[: N * stride].view(N, stride).to(torch.float32)
+        assert bool((whole[:, P:] == 512.0).all()) and bool((bufA[N * stride:].to(torch.float32) == 512.0).all())
+
+
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
 def test_fused_full_size_matches_single_rounds(cfg):
     """Full-size workloads: the fused path reproduces the single-round path bit for bit."""
