@@ -307,6 +307,19 @@ def main() -> int:
                          f"columns (all {w.N} peers, fp64 state), {cpu_s:.2f} s of oracle time",
                "rounds_per_s_full_width": round(cpu_steps * w.rounds / cpu_s * cpu_cols / w.P, 4)}
         log(f"[bench] cpu oracle: {cpu['value']} GB/s on {threads} threads ({cpu_s:.1f}s, {cpu_steps} steps)")
+        if args.config in (1, 2):
+            # the small workloads also on ONE host thread (about 5 s)
+            one_s, one_bytes, one_steps = 0.0, 0.0, 0
+            while one_s < 5.0 and one_steps < 64:
+                t_first = (cpu_steps + one_steps) * w.rounds
+                masks_k = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, w.N, t_first, w.rounds)
+                t1 = time.perf_counter()
+                orc.run(ref, w.M, w.d, t_first, w.rounds, masks_k, threads=1, slab=cpu_cols)
+                one_s += time.perf_counter() - t1
+                one_bytes += float((2.0 * s * cpu_cols * live_in_groups(masks_k, w.M, w.d, t_first)).sum())
+                one_steps += 1
+            cpu["one_thread_gbps"] = round(one_bytes / one_s / 1e9, 3)
+            log(f"[bench] cpu oracle on one thread: {cpu['one_thread_gbps']} GB/s ({one_s:.1f}s, {one_steps} steps)")
 
     traffic = read_traffic(os.path.join(ROOT, "profiles", f"group_mean_cfg{args.config}.txt"))
     out = {
