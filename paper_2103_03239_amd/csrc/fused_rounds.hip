@@ -672,11 +672,16 @@ bool plan_with(int bpc, int dtype, int64_t N, int32_t M, int32_t d, int64_t P, i
         if (rounds < 2) return false;
     }
     p.rounds = rounds;
-    // When the loads of the next tile are issued (measured on MI355X): a block
-    // that has the compute unit to itself and many rounds to run does best
-    // issuing them in four portions, after each of the first four rounds;
-    // otherwise all of them before the first round.
-    p.spread = (bpc == 1 && rounds >= 4) ? 4 : 0;
+    // One block per compute unit means many rows of few bytes each (1024 x 128 B on a
+    // 32 x 32 grid): HBM serves that pattern at little more than half the rate of the
+    // single-round kernel, so a pass of only two rounds is slower than two single rounds
+    // (measured: 10.6 ms against 9.0 ms on 16 GiB); from three rounds on the pass wins.
+    if (bpc == 1 && rounds < 3) return false;
+    // When the loads of the next tile are issued (measured on MI355X): two blocks per
+    // compute unit do best issuing them all before the first round; a block that has the
+    // compute unit to itself issues them in 2 or 4 portions, one after each of the first
+    // rounds, once there are enough rounds to spread them over.
+    p.spread = bpc == 1 ? (rounds >= 7 ? 4 : rounds >= 5 ? 2 : 0) : 0;
     const int64_t fixed = fixed_lds(rounds, rows, p.groups, F);
     int64_t budget = kLdsBytes - fixed;                          // LDS left for the tile ...
     const int64_t reg_tile = static_cast<int64_t>(kThreads) * kPrefetch * 16;   // ... and what the prefetch registers hold
