@@ -93,9 +93,10 @@ typedef struct {
  * a slice of columns is closed under rounds on those axes, so it is loaded
  * once, averaged F times on chip (any number of times when F = d) and stored
  * once.  The state after a fused pass is bit-identical to the state after the
- * same rounds run one by one.  Where fusion does not apply (rows not 16-byte
- * aligned, a sub-grid too tall for on-chip memory, a single round left) the
- * rounds run one by one. */
+ * same rounds run one by one.  Where fusion does not apply or does not pay
+ * (rows not 16-byte aligned, a sub-grid too tall for on-chip memory, a single
+ * round left, two rounds on a sub-grid so tall that its rows get only 128
+ * bytes on chip) the rounds run one by one. */
 enum {
     MOSHPIT_RUN_DEFAULT = 0,
     MOSHPIT_RUN_FUSED   = 1
