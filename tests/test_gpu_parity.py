@@ -831,6 +831,42 @@ def test_sgd_quadratic_mean_trajectory():
     assert float((X - X.mean(dim=0)).abs().max()) <= 1e-5
 
 
+def test_rounds_replayed_from_a_hip_graph():
+    """The round loop captured in a HIP graph (device masks, so a round is kernel launches
+    only) and replayed: every replay, with eager work and synchronisations between the
+    replays, gives the bits of the eager loop."""
+    M, d, P, rounds = 16, 2, 5_000, 6
+    N = M ** d
+    w = inputs.Workload("graph", N, M, d, P, 0, "peer_offset", inputs.KIND_IID, 0.1, 0, rounds, 31, 32)
+    say("hip graph replay")
+    X0 = inputs.make_state(w, DEV)
+    masks = torch.from_numpy(orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, N, 0, rounds)).to(DEV)
+    side = torch.cuda.Stream()
+    X = X0.clone()
+    with binding.Moshpit(N, P, M, d, 0) as m:
+        m.bind_state(X, stream=side)
+        with torch.cuda.stream(side):
+            for t in range(rounds):                       # eager reference (also the warm-up launches)
+                m.round_dev(t, masks[t])
+        side.synchronize()
+        want = X.clone()
+        graph = torch.cuda.CUDAGraph()
+        X.copy_(X0)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for t in range(rounds):
+                m.round_dev(t, masks[t])
+        for replay in range(3):
+            X.copy_(X0)
+            scratch = (X0 * 2.0).sum()                    # unrelated eager work between replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(X, want), f"replay {replay} differs from the eager rounds"
+            assert bool(torch.isfinite(scratch))
+        m.sync()
+
+
 # --------------------------------------------------------------------------
 # streams and several handles
 # --------------------------------------------------------------------------
