@@ -125,7 +125,11 @@ int moshpit_bind_state(moshpit_ctx *h, void *state_dev, int64_t row_stride_elems
 int moshpit_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host);
 
 /* Same, with the mask already in device memory (device, N bytes, must stay
- * unchanged until the round has run; NULL = all peers take part). */
+ * unchanged until the round has run; NULL = all peers take part).  The call
+ * only launches kernels on the bound stream, so it may be recorded into a HIP
+ * graph by a caller that captures that stream; run one round of each axis
+ * outside the capture first (the first launch of a kernel shape also sets a
+ * function attribute, which is not a stream operation). */
 int moshpit_round_dev(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev);
 
 /* Rounds t0 .. t0+rounds-1 (the loop of Alg. 1) under a failure schedule
