@@ -365,8 +365,8 @@ int oracle_skip_filter(int64_t N, int32_t M, int32_t d, int64_t t, const uint8_t
 /*
  * The simplified scheme analysed in Thm 3.2 (and compared in Sec. 4.1): in
  * every iteration the peers are permuted at random and the permutation is cut
- * into consecutive groups; every group averages (proof of Thm 3.2, App. C.3:
- * "we generate a random permutation and take contiguous subgroups").
+ * into consecutive groups; every group averages (the construction used in the
+ * proof of Thm 3.2, App. C.3).
  *
  * The permutation of round t orders the peers by the 64-bit key
  *   key(seed,t,i) = mix( mix(seed + 0xD1B54A32D192ED03*(t+1)) ^ i ),

@@ -42,7 +42,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # MOSHPIT_ORACLE_LIB: another build of moshpit_oracle.c to load instead (the
+        # sanitizer test points it at an ASan/UBSan build of the same source)
+        lib = ctypes.CDLL(os.environ.get("MOSHPIT_ORACLE_LIB") or build())
         lib.oracle_digits.argtypes = [_i64, _i32, _i32, _ptr]
         lib.oracle_digits.restype = None
         lib.oracle_group_keys.argtypes = [_i64, _i32, _i32, _i64, _ptr]

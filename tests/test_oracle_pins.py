@@ -846,3 +846,59 @@ def test_quantize_matches_torch_rounding():
     orc.quantize(B, 1)
     want = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
     assert np.array_equal(B[:, 0], want)
+
+
+def test_run_quantized_mode_hand_case():
+    """The storage-quantised mode of a run, bfloat16, by hand on a 2x2 grid: every mean
+    below falls exactly half way between two bfloat16 numbers, so round-to-nearest-even
+    decides (a mode that truncates, rounds half away from zero or forgets to round
+    between rounds gives other numbers).  Spacing of bfloat16 is 2^-7 in [1,2), 2^-6 in [2,4).
+      round 0 (axis 0): (1, 1+2^-7) -> 1+2^-8 -> 1 (even);  (3+2^-6, 3+2^-5) -> 3+1.5*2^-6 -> 3+2^-5 (even)
+      round 1 (axis 1): (1, 3+2^-5) -> 2+2^-6 exactly representable
+    The unquantised run keeps 1+2^-8 and 3+1.5*2^-6 and ends on 2 + 2^-9 + 1.5*2^-7."""
+    x0 = np.array([[1.0], [1.0 + 2.0 ** -7], [3.0 + 2.0 ** -6], [3.0 + 2.0 ** -5]])
+    q = x0.copy()
+    dist = orc.run(q, 2, 2, 0, 1, None, quantize_dtype=1, want_dist=True)
+    assert q[:, 0].tolist() == [1.0, 1.0, 3.0 + 2.0 ** -5, 3.0 + 2.0 ** -5]
+    m = 2.0 + 2.0 ** -6
+    assert dist[1] == ((1 - m) ** 2 * 2 + (3 + 2.0 ** -5 - m) ** 2 * 2) / 4
+    orc.run(q, 2, 2, 1, 1, None, quantize_dtype=1)
+    assert q[:, 0].tolist() == [m] * 4
+    full = x0.copy()
+    orc.run(full, 2, 2, 0, 2, None)
+    assert full[:, 0].tolist() == [2.0 + 2.0 ** -9 + 1.5 * 2.0 ** -7] * 4
+    # binary32: the mean of 1 and 1+2^-23 is a tie that goes to the even neighbour, 1
+    y = np.array([[1.0], [1.0 + 2.0 ** -23], [5.0], [5.0]])
+    orc.run(y, 2, 2, 0, 1, None, quantize_dtype=0)
+    assert y[:, 0].tolist() == [1.0, 1.0, 5.0, 5.0]
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_run_quantized_mode_rounds_every_round(dtype):
+    """After every round of a quantised run the state holds storage-type numbers only
+    (checked with torch's conversion, not the oracle's), peers that sit a round out keep
+    their bits, and the run equals the rounds taken one at a time with torch doing the
+    rounding in between."""
+    torch = pytest.importorskip("torch")
+    tt = torch.float32 if dtype == 0 else torch.bfloat16
+    M, d, W, rounds = 3, 2, 40, 5
+    N = M ** d
+    rng = np.random.default_rng(5 + dtype)
+    X0 = torch.from_numpy(rng.normal(size=(N, W))).to(tt).to(torch.float64).numpy().copy()
+    masks = (rng.random((rounds, N)) > 0.3).astype(np.uint8)
+    A = X0.copy()
+    dist = orc.run(A, M, d, 1, rounds, masks, quantize_dtype=dtype, want_dist=True)
+    B = X0.copy()
+    want_dist = [float(((B - B.mean(axis=0)) ** 2).sum() / N)]
+    for r in range(rounds):
+        before = B.copy()
+        orc.round_(B, M, d, 1 + r, masks[r])
+        B = torch.from_numpy(B).to(tt).to(torch.float64).numpy().copy()
+        assert np.array_equal(B[masks[r] == 0], before[masks[r] == 0])
+        want_dist.append(float(((B - B.mean(axis=0)) ** 2).sum() / N))
+    assert np.array_equal(A, B)
+    assert np.allclose(dist, want_dist, rtol=1e-12, atol=0)
+    plain = X0.copy()
+    orc.run(plain, M, d, 1, rounds, masks)
+    assert not np.array_equal(plain, A), "the quantised mode must differ from the fp64 mode"
+    assert np.abs(plain - A).max() <= (2.0 ** -22 if dtype == 0 else 2.0 ** -6) * np.abs(X0).max()
