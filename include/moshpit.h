@@ -152,6 +152,32 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
  * GPU.  out_host: host, one double. */
 int moshpit_dist_to_mean(moshpit_ctx *h, double *out_host);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * serving loops, harnesses that forbid hipMalloc): the average distortion of
+ * moshpit_dist_to_mean without a handle and without any allocation, host
+ * synchronisation or copy.  The partial sums of its first kernel live in a
+ * fixed 1 MiB array inside the library's code object (one copy per GPU, held
+ * until the process ends) instead of the handle's scratch.
+ * state_dev: device, [N][row_stride_elems], P valid elements per row, dtype
+ * MOSHPIT_F32 / MOSHPIT_BF16, borrowed until the queued work has run.
+ * out_dev: device, one double, 8-byte aligned; written by the second kernel.
+ * hip_stream: a hipStream_t or NULL; the two kernels are queued there and the
+ * call returns at once.  Same kernels, same order of additions, hence the same
+ * bits as moshpit_dist_to_mean.
+ * Limit: at most 131072 partial sums, i.e. P <= 33,554,432 binary32 or
+ * 67,108,864 bfloat16 columns when rows are 16-byte aligned (one partial per
+ * 64 vectors of 16 bytes), P <= 8,388,608 otherwise (one per 64 elements);
+ * beyond that MOSHPIT_EINVAL and nothing is queued.
+ * All calls on one GPU share the one array: calls that may overlap in time on
+ * the same GPU (different streams, different threads) race and must be ordered
+ * by the caller.  Nothing needs clearing between calls: every partial that is
+ * read has been written by the same call.  The array's address is looked up
+ * once per device (at moshpit_create, else at the first call on that device);
+ * make that first call outside a graph capture.
+ * Errors: message through moshpit_last_error(NULL). */
+int moshpit_dist_to_mean_static(const void *state_dev, int64_t N, int64_t P, int64_t row_stride_elems,
+                                int32_t dtype, void *hip_stream, double *out_dev);
+
 /* The same measure over the peers that exist when the grid is only partly
  * filled (Sec. 3.1 after Eq. 2; the partly filled grids of Sec. 4.1 / Table 4):
  * mean and average run over the rows with present_host[i] != 0 only.  A vertex

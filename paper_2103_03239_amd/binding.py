@@ -22,7 +22,7 @@ RUN_DEFAULT, RUN_FUSED = 0, 1
 
 EXPORTS = [
     "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",
-    "moshpit_run", "moshpit_dist_to_mean", "moshpit_dist_to_mean_subset", "moshpit_group_keys", "moshpit_schedule_mask",
+    "moshpit_run", "moshpit_dist_to_mean", "moshpit_dist_to_mean_static", "moshpit_dist_to_mean_subset", "moshpit_group_keys", "moshpit_schedule_mask",
     "moshpit_dynamic_reset", "moshpit_dynamic_round", "moshpit_dynamic_keys", "moshpit_local_step", "moshpit_sgd_round", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_refresh", "moshpit_refresh_donors", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
 ]
 
@@ -67,6 +67,7 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_round_dev.argtypes = [vp, i64, vp]
     lib.moshpit_run.argtypes = [vp, i64, i32, ctypes.POINTER(_CSchedule), i32, vp, vp]
     lib.moshpit_dist_to_mean.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+    lib.moshpit_dist_to_mean_static.argtypes = [vp, i64, i64, i64, i32, vp, vp]
     lib.moshpit_dist_to_mean_subset.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.moshpit_group_keys.argtypes = [vp, i64, vp]
     lib.moshpit_schedule_mask.argtypes = [vp, ctypes.POINTER(_CSchedule), i64, i32, vp]
@@ -308,3 +309,20 @@ def copy_probe(dst, src, stream=None) -> None:
     rc = load_library().moshpit_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream)
     if rc != 0:
         raise MoshpitError(f"copy_probe failed ({rc})")
+
+
+def dist_to_mean_static(X, out, stream=None) -> None:
+    """Queue the allocation-free distortion of the [N, P] GPU tensor X (float32 or bfloat16,
+    unit column stride) into out (GPU tensor holding one float64).  Returns without waiting."""
+    import torch
+    if X.dim() != 2 or X.stride(1) != 1 or not X.is_cuda or X.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("state tensor has the wrong dtype, shape or device")
+    if out.dtype != torch.float64 or out.numel() != 1 or not out.is_cuda:
+        raise ValueError("out must be one float64 on the GPU")
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device)
+    lib = load_library()
+    rc = lib.moshpit_dist_to_mean_static(X.data_ptr(), X.shape[0], X.shape[1], X.stride(0),
+                                         F32 if X.dtype == torch.float32 else BF16, stream.cuda_stream, out.data_ptr())
+    if rc != 0:
+        raise MoshpitError(f"dist_to_mean_static failed ({rc}): {lib.moshpit_last_error(None).decode()}")

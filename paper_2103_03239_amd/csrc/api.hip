@@ -239,6 +239,8 @@ int moshpit_create(int64_t N, int64_t P, int32_t M, int32_t d, int32_t dtype, mo
     if (!h) return fail(nullptr, MOSHPIT_ENOMEM, "out of host memory");
     h->N = N; h->P = P; h->M = M; h->d = d; h->dtype = dtype;
     hipError_t e = hipGetDevice(&h->device);
+    double *static_partials = nullptr;          // set-up of moshpit_dist_to_mean_static on this device
+    if (e == hipSuccess) e = static_scratch(&static_partials);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&h->d_round_mask), static_cast<size_t>(N));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&h->d_keys), static_cast<size_t>(N) * sizeof(int32_t));
     if (e != hipSuccess) {
@@ -417,6 +419,33 @@ int moshpit_dist_to_mean(moshpit_ctx *h, double *out_host)
     if (rc != MOSHPIT_OK) return rc;
     HIP_TRY(h, hipMemcpyAsync(out_host, h->d_dist, sizeof(double), hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return MOSHPIT_OK;
+}
+
+int moshpit_dist_to_mean_static(const void *state_dev, int64_t N, int64_t P, int64_t row_stride_elems,
+                                int32_t dtype, void *hip_stream, double *out_dev)
+{
+    if (!state_dev || !out_dev) return fail(nullptr, MOSHPIT_EINVAL, "state or output pointer is NULL");
+    if (N < 1 || P < 1 || row_stride_elems < P) return fail(nullptr, MOSHPIT_EINVAL, "bad shape: N, P >= 1 and row stride >= P");
+    if (dtype != MOSHPIT_F32 && dtype != MOSHPIT_BF16) return fail(nullptr, MOSHPIT_EINVAL, "unknown dtype %d", dtype);
+    const int64_t esize = dtype == MOSHPIT_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(state_dev) % esize != 0)
+        return fail(nullptr, MOSHPIT_EINVAL, "state pointer is not aligned to the element size");
+    if (reinterpret_cast<uintptr_t>(out_dev) % sizeof(double) != 0)
+        return fail(nullptr, MOSHPIT_EINVAL, "output pointer is not aligned to 8 bytes");
+    const int64_t need = dist_partials_count(dtype, P, row_stride_elems, state_dev);
+    if (need > kStaticPartials)
+        return fail(nullptr, MOSHPIT_EINVAL,
+                    "rows of %lld elements need %lld partial sums, the static scratch holds %lld "
+                    "(at most %lld columns in 16-byte-aligned rows): use moshpit_dist_to_mean",
+                    (long long)P, (long long)need, (long long)kStaticPartials,
+                    (long long)(kStaticPartials * 64 * (16 / esize)));
+    double *partials = nullptr;
+    hipError_t e = static_scratch(&partials);
+    if (e == hipSuccess)
+        e = launch_dist_to_mean(state_dev, dtype, N, P, row_stride_elems, partials, out_dev, nullptr, 0, N,
+                                static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(nullptr, MOSHPIT_EHIP, "moshpit_dist_to_mean_static: %s", hipGetErrorString(e));
     return MOSHPIT_OK;
 }
 

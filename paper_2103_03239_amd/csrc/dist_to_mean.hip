@@ -14,13 +14,26 @@
 // rows w, w+W, ... with 8 non-temporal row loads in flight each, then combine their per-column sums through LDS, reduce across lanes
 // and write ONE partial per block.  A second one-block kernel adds the partials
 // in a fixed order, so the result does not depend on scheduling.
+#include <mutex>
+
 #include "moshpit_internal.h"
+
+// Partial sums of the allocation-free entry point: one double per block of the
+// first kernel, kept in the code object so that no call ever allocates.  Every
+// GPU the library runs on holds its own copy (1 MiB) at its own address until
+// the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the kernels get the address that call returns.
+static __device__ __align__(256) double scratch[moshpit::kStaticPartials];
 
 namespace moshpit {
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double *g_scratch_ptr[kMaxDevices] = {};     // device address of `scratch`, per device
 
 constexpr int kMaxWaves = 16;      // waves per block: 1, 2, 4, 8 or 16
 constexpr int kRowsInFlight = 8;   // row loads issued before the first use
@@ -223,6 +236,24 @@ hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, i
     }
     dist_final_kernel<<<dim3(1), dim3(256), 0, stream>>>(partials, s.blocks_vec + s.blocks_tail, n, out);
     return hipGetLastError();
+}
+
+hipError_t static_scratch(double **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (ptr == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<double *>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
 }  // namespace moshpit

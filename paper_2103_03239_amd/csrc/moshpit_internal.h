@@ -58,6 +58,12 @@ hipError_t launch_dist_to_mean(const void *X, int dtype, int64_t N, int64_t P, i
                                double *partials, double *out, const uint8_t *present, int64_t first, int64_t n,
                                hipStream_t stream);
 
+// Partial sums the allocation-free distortion entry point can hold, and the device
+// address of the array that holds them on the current device (looked up once per
+// device; allocates nothing).
+constexpr int64_t kStaticPartials = 131072;
+hipError_t static_scratch(double **out);
+
 // Queue the failure-schedule generator: masks[r][i] (device, rounds*N bytes).
 hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down, int64_t N, int64_t t0,
                            int rounds, uint8_t *masks, hipStream_t stream);
