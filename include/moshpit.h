@@ -62,7 +62,12 @@ enum {
  *                             nothing meanwhile and is present again (with its
  *                             stale vector, drawing again) from s+down_rounds;
  *                             the recursion starts at round 0;
- * kind MOSHPIT_SCHED_EXPLICIT masks are given by the caller. */
+ * kind MOSHPIT_SCHED_EXPLICIT masks are given by the caller.
+ * A REJOIN schedule depends on its past.  The handle keeps, per peer, the
+ * rounds it still sits out at the end of the last schedule it generated, so a
+ * run (or moshpit_schedule_mask) that starts at or after that round with the
+ * same seed, p and down_rounds goes on from there and costs time proportional
+ * to the rounds in between; any other start walks the rounds from 0 once. */
 enum {
     MOSHPIT_SCHED_NONE = 0, MOSHPIT_SCHED_IID = 1,
     MOSHPIT_SCHED_REJOIN = 2, MOSHPIT_SCHED_EXPLICIT = 3
@@ -121,7 +126,10 @@ int moshpit_bind_state(moshpit_ctx *h, void *state_dev, int64_t row_stride_elems
 /* One averaging round t >= 0 (Alg. 1, one pass of its loop body; App. C.3's
  * group-average formula with the group J_{i,t} of App. C.4).
  * alive_host: host, N bytes, non-zero = the peer takes part; NULL = all do.
- * The mask is copied before the call returns; the round itself is queued. */
+ * The mask has been read completely when the call returns, whether it lives in
+ * pageable or in pinned host memory (the library copies it into a staging
+ * buffer of its own first; the same holds for every host mask, explicit
+ * schedule and peer list below); the round itself is queued. */
 int moshpit_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host);
 
 /* Same, with the mask already in device memory (device, N bytes, must stay
@@ -206,7 +214,7 @@ int moshpit_schedule_mask(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0,
  * averaged group by group, and every member shifts its position in its group
  * into its key: C_i := (C_i[1:], c_i).  A peer that sits the round out keeps
  * vector and key.  With all peers present, d rounds give the exact global mean
- * whatever the seed.  N <= 65536.
+ * whatever the seed.  N <= 2^24 (the round sorts 16 bytes per peer on the device).
  * moshpit_dynamic_reset restores the initial keys; moshpit_dynamic_keys copies
  * the keys to the host (N x (d-1) int32, row-major; waits). */
 int moshpit_dynamic_reset(moshpit_ctx *h);
@@ -235,7 +243,7 @@ int moshpit_sgd_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host, cons
  * with ties broken by peer index, cuts the resulting permutation into
  * consecutive groups of group_size peers (the last one may be shorter) and
  * replaces the members of every group that take part by their mean (App. C.3,
- * proof of Thm 3.2).  1 <= group_size <= 64, N <= 65536.  alive_host as in
+ * proof of Thm 3.2).  1 <= group_size <= 64, N <= 2^24.  alive_host as in
  * moshpit_round.  Queued on the bound stream.
  * moshpit_random_permutation returns the permutation of round t (host, N
  * int32, perm[r] = peer of rank r), computed by the same device kernel; waits. */

@@ -24,6 +24,7 @@ struct moshpit_ctx {
     uint8_t *d_round_mask = nullptr;   // N bytes, for moshpit_round(host mask)
     uint8_t *d_present = nullptr;      // N bytes, for moshpit_dist_to_mean_subset
     int32_t *d_perm = nullptr;         // N, peer list of the list-based rounds
+    SortItem *d_sort = nullptr;        // sort_padded_count(N) items: the random orders are sorted here
     int32_t *d_dyn = nullptr;          // chunk-index keys and their scratch (see dyn_layout)
     uint8_t *d_masks = nullptr;        // mask_rounds_cap * N bytes, for runs
     int64_t mask_rounds_cap = 0;
@@ -37,6 +38,27 @@ struct moshpit_ctx {
     double *d_dist = nullptr;          // dist_cap doubles
     int64_t dist_cap = 0;
     std::vector<hipEvent_t> events;    // 2 per timed round
+
+    // Host bytes on their way to the device (masks, peer lists): copied out of the caller's
+    // buffer into one of these pinned slots before the call returns, then sent in stream order.
+    struct StageSlot {
+        void *host = nullptr;
+        size_t cap = 0;
+        hipEvent_t sent = nullptr;     // recorded after the slot's copy to the device
+        bool pending = false;
+    };
+    static constexpr int kStageSlots = 4;
+    StageSlot stage[kStageSlots];
+    int stage_next = 0;
+
+    // Die-and-rejoin schedule carried between calls: d_away[i] = rounds peer i still sits
+    // out at the start of round away_t under (away_seed, away_threshold, away_down).
+    int32_t *d_away = nullptr;
+    bool away_valid = false;
+    uint64_t away_seed = 0;
+    uint32_t away_threshold = 0;
+    int32_t away_down = 0;
+    int64_t away_t = 0;
 
     MeanTuning tune;
     char err[512] = {0};
@@ -94,6 +116,47 @@ int check_schedule(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_
     return MOSHPIT_OK;
 }
 
+// Send `bytes` of host memory to dst_dev in stream order.  The caller's buffer has been
+// read completely when this returns, whatever kind of host memory it is (an asynchronous
+// copy straight from pinned memory would still be reading it).
+int stage_to_device(moshpit_ctx *h, void *dst_dev, const void *src_host, size_t bytes)
+{
+    if (bytes == 0) return MOSHPIT_OK;
+    moshpit_ctx::StageSlot &s = h->stage[h->stage_next];
+    h->stage_next = (h->stage_next + 1) % moshpit_ctx::kStageSlots;
+    if (s.pending) {
+        HIP_TRY(h, hipEventSynchronize(s.sent));
+        s.pending = false;
+    }
+    if (s.cap < bytes) {
+        if (s.host) HIP_TRY(h, hipHostFree(s.host));
+        s.host = nullptr;
+        s.cap = 0;
+        HIP_TRY(h, hipHostMalloc(&s.host, bytes, hipHostMallocDefault));
+        s.cap = bytes;
+    }
+    if (!s.sent) HIP_TRY(h, hipEventCreateWithFlags(&s.sent, hipEventDisableTiming));
+    std::memcpy(s.host, src_host, bytes);
+    HIP_TRY(h, hipMemcpyAsync(dst_dev, s.host, bytes, hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, hipEventRecord(s.sent, h->stream));
+    s.pending = true;
+    return MOSHPIT_OK;
+}
+
+// Rounds whose groups come from a random order sort 16 bytes per peer and address peers
+// by int32: 2^24 peers (a 256 MiB sort buffer) is where this library stops.
+constexpr int64_t kMaxOrderedPeers = int64_t(1) << 24;
+
+int reserve_sort(moshpit_ctx *h)
+{
+    if (h->N > kMaxOrderedPeers)
+        return fail(h, MOSHPIT_EINVAL, "rounds over a random order of the peers support at most %lld peers",
+                    (long long)kMaxOrderedPeers);
+    if (h->d_sort) return MOSHPIT_OK;
+    HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_sort), sizeof(SortItem) * static_cast<size_t>(sort_padded_count(h->N))));
+    return MOSHPIT_OK;
+}
+
 int reserve_masks(moshpit_ctx *h, int64_t rounds)
 {
     if (rounds <= h->mask_rounds_cap) return MOSHPIT_OK;
@@ -138,14 +201,36 @@ int queue_masks(moshpit_ctx *h, const moshpit_schedule *s, int64_t t0, int32_t r
     int rc = reserve_masks(h, rounds);
     if (rc != MOSHPIT_OK || rounds == 0) return rc;
     if (s && s->kind == MOSHPIT_SCHED_EXPLICIT) {
-        HIP_TRY(h, hipMemcpyAsync(h->d_masks, s->explicit_masks, static_cast<size_t>(rounds) * h->N,
-                                  hipMemcpyHostToDevice, h->stream));
+        rc = stage_to_device(h, h->d_masks, s->explicit_masks, static_cast<size_t>(rounds) * h->N);
+        if (rc != MOSHPIT_OK) return rc;
     } else {
         const int kind = s ? s->kind : MOSHPIT_SCHED_NONE;
         const double p = s ? s->p : 0.0;
         const uint32_t threshold = static_cast<uint32_t>(std::floor(p * 16777216.0));
-        HIP_TRY(h, launch_schedule(kind, threshold, s ? s->seed : 0, s ? s->down_rounds : 0, h->N, t0, rounds,
-                                   h->d_masks, h->stream));
+        const uint64_t seed = s ? s->seed : 0;
+        const int32_t down = s ? s->down_rounds : 0;
+        int64_t s_begin = 0;
+        const int32_t *away_in = nullptr;
+        if (kind == MOSHPIT_SCHED_REJOIN) {
+            // go on from the state a previous call left, when it belongs to this schedule and is not past t0
+            if (!h->d_away)
+                HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_away), sizeof(int32_t) * static_cast<size_t>(h->N)));
+            if (h->away_valid && h->away_seed == seed && h->away_threshold == threshold && h->away_down == down &&
+                h->away_t <= t0 && h->away_t > 0) {
+                s_begin = h->away_t;
+                away_in = h->d_away;
+            }
+            h->away_valid = false;
+        }
+        HIP_TRY(h, launch_schedule(kind, threshold, seed, down, h->N, t0, rounds, h->d_masks, s_begin, away_in,
+                                   kind == MOSHPIT_SCHED_REJOIN ? h->d_away : nullptr, h->stream));
+        if (kind == MOSHPIT_SCHED_REJOIN) {
+            h->away_valid = true;
+            h->away_seed = seed;
+            h->away_threshold = threshold;
+            h->away_down = down;
+            h->away_t = t0 + rounds;
+        }
     }
     if (s && s->group_skip) {
         if (s->refresh) {
@@ -195,10 +280,9 @@ int stage_refresh_masks(moshpit_ctx *h, const uint8_t *prev_host, const uint8_t 
     if (h->N > 0x7fffffffLL) return fail(h, MOSHPIT_EINVAL, "too many peers for 32-bit donor indices");
     if (!h->d_refresh_masks)
         HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_refresh_masks), 2 * static_cast<size_t>(h->N)));
-    HIP_TRY(h, hipMemcpyAsync(h->d_refresh_masks, prev_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice, h->stream));
-    HIP_TRY(h, hipMemcpyAsync(h->d_refresh_masks + h->N, cur_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice,
-                              h->stream));
-    return MOSHPIT_OK;
+    int rc = stage_to_device(h, h->d_refresh_masks, prev_host, static_cast<size_t>(h->N));
+    if (rc != MOSHPIT_OK) return rc;
+    return stage_to_device(h, h->d_refresh_masks + h->N, cur_host, static_cast<size_t>(h->N));
 }
 
 int queue_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev)
@@ -259,9 +343,15 @@ int moshpit_destroy(moshpit_ctx *h)
     if (!h) return MOSHPIT_OK;
     (void)hipStreamSynchronize(h->stream);
     for (hipEvent_t ev : h->events) (void)hipEventDestroy(ev);
+    for (moshpit_ctx::StageSlot &slot : h->stage) {
+        if (slot.sent) (void)hipEventDestroy(slot.sent);
+        if (slot.host) (void)hipHostFree(slot.host);
+    }
+    if (h->d_away) (void)hipFree(h->d_away);
     if (h->d_round_mask) (void)hipFree(h->d_round_mask);
     if (h->d_present) (void)hipFree(h->d_present);
     if (h->d_perm) (void)hipFree(h->d_perm);
+    if (h->d_sort) (void)hipFree(h->d_sort);
     if (h->d_dyn) (void)hipFree(h->d_dyn);
     if (h->d_masks) (void)hipFree(h->d_masks);
     if (h->d_masks_raw) (void)hipFree(h->d_masks_raw);
@@ -312,9 +402,8 @@ int moshpit_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host)
     if (rc != MOSHPIT_OK) return rc;
     if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
     if (!alive_host) return queue_round(h, t, nullptr);
-    HIP_TRY(h, hipMemcpyAsync(h->d_round_mask, alive_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice,
-                              h->stream));
-    // pageable host memory: the runtime has staged the bytes when the call returns
+    rc = stage_to_device(h, h->d_round_mask, alive_host, static_cast<size_t>(h->N));
+    if (rc != MOSHPIT_OK) return rc;
     return queue_round(h, t, h->d_round_mask);
 }
 
@@ -466,7 +555,8 @@ int moshpit_dist_to_mean_subset(moshpit_ctx *h, const uint8_t *present_host, dou
         return MOSHPIT_OK;
     }
     if (!h->d_present) HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_present), static_cast<size_t>(h->N)));
-    HIP_TRY(h, hipMemcpyAsync(h->d_present, present_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice, h->stream));
+    rc = stage_to_device(h, h->d_present, present_host, static_cast<size_t>(h->N));
+    if (rc != MOSHPIT_OK) return rc;
     HIP_TRY(h, launch_dist_to_mean(h->X, h->dtype, h->N, h->P, h->row_stride, h->d_partials, h->d_dist, h->d_present,
                                    first, n, h->stream));
     HIP_TRY(h, hipMemcpyAsync(out_host, h->d_dist, sizeof(double), hipMemcpyDeviceToHost, h->stream));
@@ -481,8 +571,8 @@ int queue_list_round(moshpit_ctx *h, const int32_t *index_dev, int64_t n_index, 
 {
     const uint8_t *alive_dev = nullptr;
     if (alive_host) {
-        HIP_TRY(h, hipMemcpyAsync(h->d_round_mask, alive_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice,
-                                  h->stream));
+        int rc = stage_to_device(h, h->d_round_mask, alive_host, static_cast<size_t>(h->N));
+        if (rc != MOSHPIT_OK) return rc;
         alive_dev = h->d_round_mask;
     }
     RoundGeom geom{h->N, group_size, 1, index_dev, n_index};
@@ -506,9 +596,7 @@ const uint8_t *stage_mask(moshpit_ctx *h, const uint8_t *alive_host, int *rc)
 {
     *rc = MOSHPIT_OK;
     if (!alive_host) return nullptr;
-    hipError_t e = hipMemcpyAsync(h->d_round_mask, alive_host, static_cast<size_t>(h->N), hipMemcpyHostToDevice,
-                                  h->stream);
-    if (e != hipSuccess) *rc = fail(h, MOSHPIT_EHIP, "mask copy: %s", hipGetErrorString(e));
+    *rc = stage_to_device(h, h->d_round_mask, alive_host, static_cast<size_t>(h->N));
     return h->d_round_mask;
 }
 }  // namespace
@@ -569,7 +657,8 @@ DynLayout dyn_layout(const moshpit_ctx *h)
 
 int dyn_ensure(moshpit_ctx *h)
 {
-    if (h->N > 65536) return fail(h, MOSHPIT_EINVAL, "chunk-index keys support at most 65536 peers");
+    int rc = reserve_sort(h);
+    if (rc != MOSHPIT_OK) return rc;
     if (h->d_dyn) return MOSHPIT_OK;
     DynLayout L = dyn_layout(h);
     const size_t words = static_cast<size_t>(h->N * L.kd + h->N + 2 * (L.n_keys + 1) + L.n_index);
@@ -601,7 +690,7 @@ int moshpit_dynamic_round(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_
     if (rc != MOSHPIT_OK) return rc;
     const DynLayout L = dyn_layout(h);
     HIP_TRY(h, launch_dynamic_grouping(h->N, h->M, h->d, seed, t, alive_dev, L.keys, L.packed, L.count, L.first,
-                                       L.index, L.n_index, h->stream));
+                                       L.index, L.n_index, h->d_sort, h->stream));
     RoundGeom geom{h->N, h->M, 1, L.index, L.n_index};
     HIP_TRY(h, launch_group_mean(h->X, h->dtype, h->P, h->row_stride, geom, nullptr, h->tune, h->stream));
     return MOSHPIT_OK;
@@ -625,8 +714,9 @@ int moshpit_random_permutation(moshpit_ctx *h, int64_t t, uint64_t seed, int32_t
 {
     if (!h) return MOSHPIT_EINVAL;
     if (t < 0 || !perm_host) return fail(h, MOSHPIT_EINVAL, "bad round index or NULL output");
-    if (h->N > 65536) return fail(h, MOSHPIT_EINVAL, "random groups support at most 65536 peers");
-    HIP_TRY(h, launch_random_permutation(seed, t, h->N, h->d_keys, h->stream));
+    int rc = reserve_sort(h);
+    if (rc != MOSHPIT_OK) return rc;
+    HIP_TRY(h, launch_random_permutation(seed, t, h->N, h->d_keys, h->d_sort, h->stream));
     HIP_TRY(h, hipMemcpyAsync(perm_host, h->d_keys, sizeof(int32_t) * static_cast<size_t>(h->N),
                               hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
@@ -640,9 +730,10 @@ int moshpit_random_groups_round(moshpit_ctx *h, int64_t t, uint64_t seed, int32_
     if (rc != MOSHPIT_OK) return rc;
     if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
     if (group_size < 1 || group_size > 64) return fail(h, MOSHPIT_EINVAL, "group_size must be in [1, 64]");
-    if (h->N > 65536) return fail(h, MOSHPIT_EINVAL, "random groups support at most 65536 peers");
+    rc = reserve_sort(h);
+    if (rc != MOSHPIT_OK) return rc;
     if (!h->d_perm) HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_perm), sizeof(int32_t) * static_cast<size_t>(h->N)));
-    HIP_TRY(h, launch_random_permutation(seed, t, h->N, h->d_perm, h->stream));
+    HIP_TRY(h, launch_random_permutation(seed, t, h->N, h->d_perm, h->d_sort, h->stream));
     return queue_list_round(h, h->d_perm, h->N, group_size, alive_host);
 }
 
@@ -690,8 +781,8 @@ int moshpit_grouped_round(moshpit_ctx *h, const int32_t *index_host, int64_t n_i
     }
     if (n_index == 0) return MOSHPIT_OK;
     if (!h->d_perm) HIP_TRY(h, hipMalloc(reinterpret_cast<void **>(&h->d_perm), sizeof(int32_t) * static_cast<size_t>(h->N)));
-    HIP_TRY(h, hipMemcpyAsync(h->d_perm, index_host, sizeof(int32_t) * static_cast<size_t>(n_index),
-                              hipMemcpyHostToDevice, h->stream));
+    rc = stage_to_device(h, h->d_perm, index_host, sizeof(int32_t) * static_cast<size_t>(n_index));
+    if (rc != MOSHPIT_OK) return rc;
     return queue_list_round(h, h->d_perm, n_index, group_size, alive_host);
 }
 

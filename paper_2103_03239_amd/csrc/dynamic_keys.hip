@@ -9,26 +9,15 @@
 // which the peer-list instantiation of the group-mean kernel then averages,
 // and update the keys.  Pure integer work: bit-exact against the CPU oracle.
 //
-// N is at most 65536, so ranks are found by counting (one thread per peer
-// scans all peers) instead of sorting.
+// A peer's rank among the participants that carry its key comes from one device
+// sort of the items (key, order key of the round, peer): the participants of a key
+// end up next to each other in the round's random order, and the rank is the
+// distance to the first of them.
+#include "mix64.h"
 #include "moshpit_internal.h"
 
 namespace moshpit {
 namespace {
-
-__device__ __forceinline__ uint64_t mix64(uint64_t x)
-{
-    x ^= x >> 32; x *= 0x9E3779B97F4A7C15ull;
-    x ^= x >> 29; x *= 0x6A09E667F3BCC909ull;
-    x ^= x >> 32;
-    return x;
-}
-
-// position of peer i in the random order of round t (smaller key first, ties by index)
-__device__ __forceinline__ uint64_t order_key(uint64_t seed, int64_t t, int64_t i)
-{
-    return mix64(mix64(seed + 0xD1B54A32D192ED03ull * static_cast<uint64_t>(t + 1)) ^ static_cast<uint64_t>(i));
-}
 
 // keys[i][q] = coordinate q+1 of peer i (Eq. 2): the first round groups M consecutive peers
 __global__ __launch_bounds__(256) void dyn_init_kernel(int64_t N, int32_t M, int32_t kd, int32_t *__restrict__ keys)
@@ -100,24 +89,45 @@ __global__ __launch_bounds__(1024) void dyn_scan_kernel(int64_t n_keys, int32_t 
     }
 }
 
-// rank of peer i among the participants with its key -> its slot in the padded list and its new key
-__global__ __launch_bounds__(256) void dyn_place_kernel(int64_t N, int32_t M, int32_t kd, uint64_t seed, int64_t t,
+// item of peer i: (key, order key, i) packed as hi = key << 32 | order >> 32,
+// lo = order << 32 | i; peers that sit the round out (key -1) and the padding sort last
+__global__ __launch_bounds__(256) void dyn_items_kernel(int64_t N, int64_t n_padded, uint64_t seed, int64_t t,
                                                         const int32_t *__restrict__ packed,
+                                                        SortItem *__restrict__ items)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n_padded) return;
+    SortItem it{~0ull, ~0ull};
+    if (i < N) {
+        const uint64_t order = order_key(seed, t, i);
+        it.hi = (static_cast<uint64_t>(static_cast<uint32_t>(packed[i])) << 32) | (order >> 32);
+        it.lo = (order << 32) | static_cast<uint64_t>(i);
+    }
+    items[i] = it;
+}
+
+// sorted position r -> the peer there, its rank among the participants with its key
+// (distance to the first item of that key, found by bisection), its slot in the padded
+// list and its new key
+__global__ __launch_bounds__(256) void dyn_place_kernel(int64_t N, int32_t M, int32_t kd,
+                                                        const SortItem *__restrict__ items,
                                                         const int32_t *__restrict__ first, int32_t *__restrict__ keys,
                                                         int32_t *__restrict__ index)
 {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (i >= N) return;
-    const int32_t pk = packed[i];
-    if (pk < 0) return;
-    const uint64_t ki = order_key(seed, t, i);
-    int32_t rank = 0;
-    for (int64_t j = 0; j < N; ++j) {
-        if (packed[j] != pk) continue;
-        const uint64_t kj = order_key(seed, t, j);
-        rank += (kj < ki || (kj == ki && j < i)) ? 1 : 0;
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (r >= N) return;
+    const SortItem it = items[r];
+    const uint32_t pk = static_cast<uint32_t>(it.hi >> 32);
+    if (pk == 0xffffffffu) return;                     // sits the round out
+    const int64_t i = static_cast<int64_t>(it.lo & 0xffffffffull);
+    int64_t lo = 0, hi = r;                            // smallest position whose key is pk
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (static_cast<uint32_t>(items[mid].hi >> 32) < pk) lo = mid + 1;
+        else hi = mid;
     }
-    const int32_t chunk = rank % M;                    // c_i: position within its group of at most M
+    const int64_t rank = r - lo;
+    const int32_t chunk = static_cast<int32_t>(rank % M);   // c_i: position within its group of at most M
     index[(static_cast<int64_t>(first[pk]) + rank / M) * M + chunk] = static_cast<int32_t>(i);
     if (kd > 0) {
         for (int32_t q = 0; q + 1 < kd; ++q) keys[i * kd + q] = keys[i * kd + q + 1];
@@ -136,7 +146,7 @@ hipError_t launch_dynamic_init(int64_t N, int32_t M, int32_t d, int32_t *keys, h
 
 hipError_t launch_dynamic_grouping(int64_t N, int32_t M, int32_t d, uint64_t seed, int64_t t, const uint8_t *alive,
                                    int32_t *keys, int32_t *packed, int32_t *count, int32_t *first, int32_t *index,
-                                   int64_t n_index, hipStream_t stream)
+                                   int64_t n_index, SortItem *items, hipStream_t stream)
 {
     int64_t n_keys = 1;
     for (int32_t q = 0; q + 1 < d; ++q) n_keys *= M;
@@ -148,7 +158,12 @@ hipError_t launch_dynamic_grouping(int64_t N, int32_t M, int32_t d, uint64_t see
                                                                n_index);
     dyn_count_kernel<<<dim3(blocks_n), dim3(256), 0, stream>>>(N, packed, count);
     dyn_scan_kernel<<<dim3(1), dim3(1024), 0, stream>>>(n_keys, M, count, first);
-    dyn_place_kernel<<<dim3(blocks_n), dim3(256), 0, stream>>>(N, M, d - 1, seed, t, packed, first, keys, index);
+    const int64_t n_padded = sort_padded_count(N);
+    dyn_items_kernel<<<dim3(static_cast<uint32_t>((n_padded + 255) / 256)), dim3(256), 0, stream>>>(N, n_padded, seed, t,
+                                                                                                    packed, items);
+    hipError_t e = launch_sort_items(items, n_padded, stream);
+    if (e != hipSuccess) return e;
+    dyn_place_kernel<<<dim3(blocks_n), dim3(256), 0, stream>>>(N, M, d - 1, items, first, keys, index);
     return hipGetLastError();
 }
 

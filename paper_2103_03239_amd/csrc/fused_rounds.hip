@@ -743,8 +743,6 @@ hipError_t launch_with(void *X, int dtype, const FusedPlan &plan, const uint8_t 
         {MOSHPIT_ROW(1, 2), MOSHPIT_ROW(1, 4), MOSHPIT_ROW(1, 8), MOSHPIT_ROW16(1)}};
 #undef MOSHPIT_ROW
 #undef MOSHPIT_ROW16
-    static bool raised[2][4][7] = {};
-    static int compute_units = 0;
     const int tree = tree_size(plan.M);
     const int ti = tree == 2 ? 0 : tree == 4 ? 1 : tree == 8 ? 2 : 3;
     // Every thread should have an item: prefer 4 columns per thread; if the tile
@@ -764,19 +762,11 @@ hipError_t launch_with(void *X, int dtype, const FusedPlan &plan, const uint8_t 
         }
     }
     const kernel_t kernel = table[dtype][ti][ci];
-    if (!raised[dtype][ti][ci]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_of(BPC));
-        if (e != hipSuccess) return e;
-        raised[dtype][ti][ci] = true;
-    }
-    if (compute_units == 0) {
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&compute_units, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        if (compute_units <= 0) compute_units = 256;
-    }
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kernel), lds_of(BPC));
+    if (e != hipSuccess) return e;
+    int compute_units = 0;
+    e = current_compute_units(&compute_units);
+    if (e != hipSuccess) return e;
     // persistent: BPC blocks per compute unit walk the tiles
     const int64_t slots = static_cast<int64_t>(compute_units) * BPC;
     const int64_t grid = plan.work_items < slots ? plan.work_items : slots;

@@ -18,6 +18,8 @@
 //
 // The participant bitmap of a group is built by the wave itself: lane j < M
 // reads alive[base + j*S] and a ballot gives a 64-bit mask (hence M <= 64).
+#include <cstdlib>
+
 #include "moshpit_internal.h"
 
 namespace moshpit {
@@ -124,7 +126,7 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
                                                             int64_t S, int64_t tiles, int64_t work_items,
                                                             const int32_t *__restrict__ index, int64_t n_index,
                                                             const char *__restrict__ G, int64_t g_row_bytes,
-                                                            float gamma)
+                                                            float gamma, int order)
 {
     typedef Vec<DT, VE> V;
     typedef typename V::mem_t mem_t;
@@ -132,9 +134,20 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
     const int lane = threadIdx.x & 63;
     const int kBlock = blockDim.x;
 
-    for (int64_t w = blockIdx.x; w < work_items; w += gridDim.x) {
-        const int64_t g = w / tiles;
-        const int64_t tile = w - g * tiles;
+    for (int64_t w0 = blockIdx.x; w0 < work_items; w0 += gridDim.x) {
+        int64_t w = w0;
+        if (order == 1) {            // blocks b, b+8, b+16, ... (one XCD) take consecutive work items
+            const int64_t per = (work_items + 7) >> 3;
+            w = (w0 & 7) * per + (w0 >> 3);
+            if ((w0 >> 3) >= per || w >= work_items) continue;
+        }
+        int64_t g = w / tiles;
+        int64_t tile = w - g * tiles;
+        if (order == 2) {            // group-fastest
+            const int64_t groups = work_items / tiles;
+            tile = w / groups;
+            g = w - tile * groups;
+        }
         int64_t base = 0;
         int32_t my_row = -1;                         // IDX: the row of position `lane`
         bool takes_part = false;
@@ -259,25 +272,23 @@ hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *a
     const int64_t groups = IDX ? (geom.n_index + geom.M - 1) / geom.M : geom.N / geom.M;
     const int64_t work = groups * tiles;
     if (work <= 0) return hipSuccess;
-    const int64_t grid = work < 0x7fffffffLL ? work : 0x7fffffffLL;
+    int64_t grid = work < 0x7fffffffLL ? work : 0x7fffffffLL;
+    const int order = std::getenv("MOSHPIT_K1_ORDER") ? std::atoi(std::getenv("MOSHPIT_K1_ORDER")) : 0;
+    if (order == 1) grid = ((work + 7) >> 3) << 3;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     auto kernel = group_mean_kernel<DT, VE, COLS, U, NT, IDX, SGD>;
     size_t lds = 0;
     if (waves_per_cu > 0 && waves_per_cu < 32) {
         int blocks_per_cu = waves_per_cu / (block / 64);
         if (blocks_per_cu < 1) blocks_per_cu = 1;
         lds = static_cast<size_t>(kLdsPerCu / blocks_per_cu) / 512 * 512;
-        static bool raised = false;                 // per instantiation
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kernel), kLdsPerCu);
+        if (e != hipSuccess) return e;
     }
     kernel<<<dim3(static_cast<uint32_t>(grid)), dim3(block), lds, stream>>>(X, row_bytes, nvec, alive, geom.M,
                                                                             geom.S, tiles, work, geom.index,
                                                                             geom.n_index, geom.grad, geom.grad_row_bytes,
-                                                                            geom.gamma);
+                                                                            geom.gamma, order);
     return hipGetLastError();
 }
 
@@ -440,37 +451,6 @@ hipError_t launch_local_step(void *X, int dtype, int64_t N, int64_t P, int64_t r
                                            alive, gamma, stream)
                       : launch_local<1, 1>(x + tail0 * esize, row_bytes, g + tail0 * esize, g_row_bytes, P - tail0, N,
                                            alive, gamma, stream);
-}
-
-// ---- plain copy, the streaming ceiling the round kernel is measured against ----
-
-namespace {
-constexpr int kBlock = 256;
-__global__ __launch_bounds__(kBlock) void copy_probe_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
-                                                            int64_t nvec)
-{
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock * 4;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock * 4 + threadIdx.x; i < nvec; i += stride) {
-        u32x4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (i + u * kBlock < nvec) v[u] = src[i + u * kBlock];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (i + u * kBlock < nvec) dst[i + u * kBlock] = v[u];
-    }
-}
-}  // namespace
-
-hipError_t launch_copy_probe(void *dst, const void *src, int64_t nbytes, hipStream_t stream)
-{
-    const int64_t nvec = nbytes / 16;
-    if (nvec <= 0) return hipSuccess;
-    int64_t blocks = (nvec + kBlock * 4 - 1) / (kBlock * 4);
-    if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
-    copy_probe_kernel<<<dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0, stream>>>(
-        static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), nvec);
-    return hipGetLastError();
 }
 
 }  // namespace moshpit

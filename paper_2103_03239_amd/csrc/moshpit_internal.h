@@ -9,6 +9,27 @@
 
 namespace moshpit {
 
+// Per-device launch facts, looked up once per device and kept in a table guarded by a
+// mutex (handles on different devices, and threads making their first launch at the same
+// time, do not disturb each other).
+// ensure_dynamic_lds: allow `kernel` to be launched with up to `bytes` of dynamic LDS on
+// the current device (a function attribute; set once per kernel and device).
+// current_compute_units: number of compute units of the current device.
+hipError_t ensure_dynamic_lds(const void *kernel, int bytes);
+hipError_t current_compute_units(int *out);
+
+// 128-bit item of the device sort, compared as (hi, lo).
+struct SortItem {
+    uint64_t hi, lo;
+};
+
+// Items the sort works on for n real ones: the next power of two, at least 4096.
+int64_t sort_padded_count(int64_t n);
+
+// Queue the sort of items[0..n_padded) (device; n_padded from sort_padded_count, the
+// caller fills the padding with items that compare last), ascending, in place.
+hipError_t launch_sort_items(SortItem *items, int64_t n_padded, hipStream_t stream);
+
 // Launch shape of the group-mean kernel.  cols = 128-bit vectors per thread per
 // row, unroll = rows whose loads are issued before the first add, nt =
 // non-temporal loads and stores, block = threads per block (64/128/256),
@@ -65,18 +86,24 @@ constexpr int64_t kStaticPartials = 131072;
 hipError_t static_scratch(double **out);
 
 // Queue the failure-schedule generator: masks[r][i] (device, rounds*N bytes).
+// Die-and-rejoin schedules (kind 2) depend on the past: the walk starts at round
+// s_begin <= t0 from away_in (device, N int32: rounds each peer still sits out at the
+// start of round s_begin; nullptr = round 0, nobody away) and leaves the state at the
+// start of round t0 + rounds in away_out (device, N int32, may equal away_in; nullptr =
+// not wanted).  The other kinds ignore the three arguments.
 hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down, int64_t N, int64_t t0,
-                           int rounds, uint8_t *masks, hipStream_t stream);
+                           int rounds, uint8_t *masks, int64_t s_begin, const int32_t *away_in, int32_t *away_out,
+                           hipStream_t stream);
 
 // Alg. 1 with chunk-index keys.  keys: device, N x (d-1) int32.  init writes the initial
 // keys; grouping turns (keys, alive, seed, t) into the padded peer list index[0..n_index)
 // (group g = entries [g*M, (g+1)*M), unused entries -1; n_index >= (N/M + M^(d-1)) * M) and
 // shifts each participant's chunk index into its key.  packed: N int32, count/first:
-// M^(d-1)+1 int32 each (device scratch).
+// M^(d-1)+1 int32 each, items: sort_padded_count(N) entries (device scratch).
 hipError_t launch_dynamic_init(int64_t N, int32_t M, int32_t d, int32_t *keys, hipStream_t stream);
 hipError_t launch_dynamic_grouping(int64_t N, int32_t M, int32_t d, uint64_t seed, int64_t t, const uint8_t *alive,
                                    int32_t *keys, int32_t *packed, int32_t *count, int32_t *first, int32_t *index,
-                                   int64_t n_index, hipStream_t stream);
+                                   int64_t n_index, SortItem *items, hipStream_t stream);
 
 // Queue the group-skip filter on masks[rounds][N] (device, in place) for rounds t0..
 hipError_t launch_skip_filter(uint8_t *masks, int64_t N, int32_t M, int32_t d, int64_t t0, int rounds,
@@ -92,9 +119,11 @@ hipError_t launch_refresh_plan(const uint8_t *prev, const uint8_t *cur, int64_t 
 hipError_t launch_refresh_copy(void *X, int dtype, int64_t N, int64_t P, int64_t row_stride, const int32_t *donor,
                                const int32_t *returning, const int32_t *counts, hipStream_t stream);
 
-// Queue the random-permutation kernel: perm[r] = peer of rank r when the peers
+// Queue the random-permutation kernels: perm[r] = peer of rank r when the peers
 // are ordered by their 64-bit key of (seed, t), ties by index (device, N int32).
-hipError_t launch_random_permutation(uint64_t seed, int64_t t, int64_t N, int32_t *perm, hipStream_t stream);
+// items: device scratch, sort_padded_count(N) entries.
+hipError_t launch_random_permutation(uint64_t seed, int64_t t, int64_t N, int32_t *perm, SortItem *items,
+                                     hipStream_t stream);
 
 // Queue the group-key kernel: keys[i] (device, N int32) for axis a, S = M^a.
 hipError_t launch_group_keys(int64_t N, int32_t M, int64_t S, int32_t *keys, hipStream_t stream);

@@ -5,29 +5,17 @@
 // round t-1; the up-to-date peers it can reach are those present in both
 // rounds; its donor is the (u mod c)-th of these c candidates in ascending
 // index, u = mix(mix(seed + 0xA0761D6478BD642F*(t+1)) ^ i) with the mixer of
-// the failure schedule.  Two kernels: an integer one that draws the donors and
-// lists the returning peers, and a copy kernel that moves 2*s*P bytes per
-// returning peer at streaming rate.  Donors never return themselves, so the
-// copies are independent of each other and run in place.
+// the failure schedule.  This file holds the integer kernel that draws the donors
+// and lists the returning peers; the rows are then copied by the streaming copy
+// kernel (2*s*P bytes per returning peer).  Donors never return themselves, so
+// the copies are independent of each other and run in place.
+#include "mix64.h"
 #include "moshpit_internal.h"
 
 namespace moshpit {
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int kPlanThreads = 1024;
-constexpr int kCopyThreads = 256;
-constexpr int kCopyVectors = 8;                               // 128-bit vectors per thread and chunk
-constexpr int64_t kChunkBytes = int64_t(kCopyThreads) * kCopyVectors * 16;   // 32 KiB of a row per block
-
-__device__ __forceinline__ uint64_t mix64(uint64_t x)
-{
-    x ^= x >> 32; x *= 0x9E3779B97F4A7C15ull;
-    x ^= x >> 29; x *= 0x6A09E667F3BCC909ull;
-    x ^= x >> 32;
-    return x;
-}
 
 // Stable compaction step of one block: every thread passes `flag`, gets the
 // number of set flags of the threads before it; *total gets the block's count.
@@ -95,46 +83,6 @@ __global__ __launch_bounds__(kPlanThreads) void refresh_plan_kernel(const uint8_
     }
 }
 
-// Block (x, y): the x-th 32 KiB chunk of the rows of returning peers y, y +
-// gridDim.y, ...  VEC: rows are 16-byte aligned (128-bit copies, the ragged end
-// of a row element by element); otherwise everything element by element.
-template <int ESIZE, bool VEC>
-__global__ __launch_bounds__(kCopyThreads) void refresh_copy_kernel(char *__restrict__ X, int64_t row_bytes,
-                                                                     int64_t valid_bytes,
-                                                                     const int32_t *__restrict__ donor,
-                                                                     const int32_t *__restrict__ returning,
-                                                                     const int32_t *__restrict__ counts)
-{
-    typedef typename std::conditional<ESIZE == 4, uint32_t, uint16_t>::type elem_t;
-    const int32_t n_ret = counts[1];
-    const int64_t c0 = static_cast<int64_t>(blockIdx.x) * kChunkBytes;
-    const int64_t c1 = c0 + kChunkBytes < valid_bytes ? c0 + kChunkBytes : valid_bytes;
-    for (int32_t r = blockIdx.y; r < n_ret; r += gridDim.y) {
-        const int64_t i = returning[r];
-        const char *src = X + static_cast<int64_t>(donor[i]) * row_bytes;
-        char *dst = X + i * row_bytes;
-        if (VEC) {
-            const int64_t v_end = c1 / 16 * 16;
-            u32x4 val[kCopyVectors];
-#pragma unroll
-            for (int k = 0; k < kCopyVectors; ++k) {
-                const int64_t o = c0 + (static_cast<int64_t>(k) * kCopyThreads + threadIdx.x) * 16;
-                if (o < v_end) val[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
-            }
-#pragma unroll
-            for (int k = 0; k < kCopyVectors; ++k) {
-                const int64_t o = c0 + (static_cast<int64_t>(k) * kCopyThreads + threadIdx.x) * 16;
-                if (o < v_end) __builtin_nontemporal_store(val[k], reinterpret_cast<u32x4 *>(dst + o));
-            }
-            for (int64_t o = v_end + static_cast<int64_t>(threadIdx.x) * ESIZE; o < c1; o += kCopyThreads * ESIZE)
-                *reinterpret_cast<elem_t *>(dst + o) = *reinterpret_cast<const elem_t *>(src + o);
-        } else {
-            for (int64_t o = c0 + static_cast<int64_t>(threadIdx.x) * ESIZE; o < c1; o += kCopyThreads * ESIZE)
-                *reinterpret_cast<elem_t *>(dst + o) = *reinterpret_cast<const elem_t *>(src + o);
-        }
-    }
-}
-
 }  // namespace
 
 hipError_t launch_refresh_plan(const uint8_t *prev, const uint8_t *cur, int64_t N, uint64_t seed, int64_t t,
@@ -144,30 +92,6 @@ hipError_t launch_refresh_plan(const uint8_t *prev, const uint8_t *cur, int64_t 
     if (N <= 0) return hipSuccess;
     refresh_plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, stream>>>(prev, cur, N, seed, t, candidates, donor,
                                                                     returning, counts);
-    return hipGetLastError();
-}
-
-hipError_t launch_refresh_copy(void *X, int dtype, int64_t N, int64_t P, int64_t row_stride, const int32_t *donor,
-                               const int32_t *returning, const int32_t *counts, hipStream_t stream)
-{
-    if (N <= 0 || P <= 0) return hipSuccess;
-    const int64_t esize = dtype == 0 ? 4 : 2;
-    const int64_t row_bytes = row_stride * esize, valid = P * esize;
-    const int64_t chunks = (valid + kChunkBytes - 1) / kChunkBytes;
-    if (chunks > 0x7fffffffLL) return hipErrorInvalidValue;
-    // the number of returning peers is known on the device only: enough rows of blocks
-    // for a few thousand peers at once, further ones are reached by the stride loop
-    const uint32_t rows = static_cast<uint32_t>(N < 4096 ? N : 4096);
-    const bool vec = reinterpret_cast<uintptr_t>(X) % 16 == 0 && row_bytes % 16 == 0;
-    const dim3 grid(static_cast<uint32_t>(chunks), rows), block(kCopyThreads);
-    char *base = static_cast<char *>(X);
-    if (dtype == 0) {
-        if (vec) refresh_copy_kernel<4, true><<<grid, block, 0, stream>>>(base, row_bytes, valid, donor, returning, counts);
-        else refresh_copy_kernel<4, false><<<grid, block, 0, stream>>>(base, row_bytes, valid, donor, returning, counts);
-    } else {
-        if (vec) refresh_copy_kernel<2, true><<<grid, block, 0, stream>>>(base, row_bytes, valid, donor, returning, counts);
-        else refresh_copy_kernel<2, false><<<grid, block, 0, stream>>>(base, row_bytes, valid, donor, returning, counts);
-    }
     return hipGetLastError();
 }
 

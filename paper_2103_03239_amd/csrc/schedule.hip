@@ -1,21 +1,15 @@
 // Integer side of a round on the device: the seeded failure schedule and the
 // group keys (Eq. 1 on the static grid).  Pure 64-bit integer arithmetic, so
 // results are bit-exact and independent of launch shape.
+#include "mix64.h"
 #include "moshpit_internal.h"
 
 namespace moshpit {
 namespace {
 
-// Counter-based generator of the failure events (the paper only says that a
+// Failure events from the counter-based generator (the paper only says that a
 // peer fails in a round with probability p, Sec. 4.1; the mixer is this
 // library's own and is stated in the public header).
-__device__ __forceinline__ uint64_t mix64(uint64_t x)
-{
-    x ^= x >> 32; x *= 0x9E3779B97F4A7C15ull;
-    x ^= x >> 29; x *= 0x6A09E667F3BCC909ull;
-    x ^= x >> 32;
-    return x;
-}
 
 __device__ __forceinline__ bool failure_event(uint64_t seed, int64_t s, int64_t i, uint32_t threshold)
 {
@@ -25,10 +19,14 @@ __device__ __forceinline__ bool failure_event(uint64_t seed, int64_t s, int64_t 
 }
 
 // One thread per peer; the thread walks the rounds because a peer's absence
-// depends on when its last one started (kind 2).
+// depends on when its last one started (kind 2).  For kind 2 the walk starts at
+// round s_begin <= t0 with away_in[i] rounds still to sit out (s_begin = 0 and
+// nothing to sit out when away_in is null), and away_out[i] receives the state
+// at the start of round t0 + rounds, from which a later call can go on.
 __global__ __launch_bounds__(256) void schedule_kernel(int kind, uint32_t threshold, uint64_t seed, int down,
                                                        int64_t N, int64_t t0, int rounds,
-                                                       uint8_t *__restrict__ masks)
+                                                       uint8_t *__restrict__ masks, int64_t s_begin,
+                                                       const int32_t *away_in, int32_t *away_out)
 {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (i >= N) return;
@@ -38,13 +36,14 @@ __global__ __launch_bounds__(256) void schedule_kernel(int kind, uint32_t thresh
         for (int r = 0; r < rounds; ++r)
             masks[static_cast<int64_t>(r) * N + i] = failure_event(seed, t0 + r, i, threshold) ? 0 : 1;
     } else {
-        int away = 0;                                    // rounds still to sit out
-        for (int64_t s = 0; s < t0 + rounds; ++s) {
+        int away = away_in != nullptr ? away_in[i] : 0;   // rounds still to sit out
+        for (int64_t s = s_begin; s < t0 + rounds; ++s) {
             if (away == 0 && failure_event(seed, s, i, threshold)) away = down;
             const uint8_t present = away == 0 ? 1 : 0;
             if (away > 0) --away;
             if (s >= t0) masks[(s - t0) * N + i] = present;
         }
+        if (away_out != nullptr) away_out[i] = away;
     }
 }
 
@@ -69,25 +68,21 @@ __global__ __launch_bounds__(64) void skip_filter_kernel(uint8_t *__restrict__ m
 // Random permutation for the random-group scheme analysed in Thm 3.2 (its proof
 // in App. C.3 draws a permutation and cuts it into consecutive groups).  Peers
 // are ordered by key(seed,t,i) = mix(mix(seed + 0xD1B54A32D192ED03*(t+1)) ^ i),
-// ties by index; thread i counts its rank against all peers (N is at most a
-// few thousand) and writes perm[rank] = i.
-__device__ __forceinline__ uint64_t order_key(uint64_t seed, int64_t t, int64_t i)
-{
-    return mix64(mix64(seed + 0xD1B54A32D192ED03ull * static_cast<uint64_t>(t + 1)) ^ static_cast<uint64_t>(i));
-}
-
-__global__ __launch_bounds__(256) void random_permutation_kernel(uint64_t seed, int64_t t, int64_t N,
-                                                                 int32_t *__restrict__ perm)
+// ties by index: the items (key, i) are sorted on the device and perm[r] is the
+// peer of the r-th item.
+__global__ __launch_bounds__(256) void permutation_items_kernel(uint64_t seed, int64_t t, int64_t N, int64_t n_padded,
+                                                                SortItem *__restrict__ items)
 {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (i >= N) return;
-    const uint64_t ki = order_key(seed, t, i);
-    int64_t rank = 0;
-    for (int64_t j = 0; j < N; ++j) {
-        const uint64_t kj = order_key(seed, t, j);
-        rank += (kj < ki || (kj == ki && j < i)) ? 1 : 0;
-    }
-    perm[rank] = static_cast<int32_t>(i);
+    if (i >= n_padded) return;
+    items[i] = i < N ? SortItem{order_key(seed, t, i), static_cast<uint64_t>(i)} : SortItem{~0ull, ~0ull};
+}
+
+__global__ __launch_bounds__(256) void permutation_extract_kernel(const SortItem *__restrict__ items, int64_t N,
+                                                                  int32_t *__restrict__ perm)
+{
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (r < N) perm[r] = static_cast<int32_t>(items[r].lo);
 }
 
 // key(i) = the base-M number formed by the digits of i other than digit a,
@@ -102,11 +97,13 @@ __global__ __launch_bounds__(256) void group_keys_kernel(int64_t N, int32_t M, i
 }  // namespace
 
 hipError_t launch_schedule(int kind, uint32_t threshold, uint64_t seed, int down, int64_t N, int64_t t0,
-                           int rounds, uint8_t *masks, hipStream_t stream)
+                           int rounds, uint8_t *masks, int64_t s_begin, const int32_t *away_in, int32_t *away_out,
+                           hipStream_t stream)
 {
     if (N <= 0 || rounds <= 0) return hipSuccess;
     const uint32_t blocks = static_cast<uint32_t>((N + 255) / 256);
-    schedule_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(kind, threshold, seed, down, N, t0, rounds, masks);
+    schedule_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(kind, threshold, seed, down, N, t0, rounds, masks,
+                                                            s_begin, away_in, away_out);
     return hipGetLastError();
 }
 
@@ -121,11 +118,16 @@ hipError_t launch_skip_filter(uint8_t *masks, int64_t N, int32_t M, int32_t d, i
     return hipGetLastError();
 }
 
-hipError_t launch_random_permutation(uint64_t seed, int64_t t, int64_t N, int32_t *perm, hipStream_t stream)
+hipError_t launch_random_permutation(uint64_t seed, int64_t t, int64_t N, int32_t *perm, SortItem *items,
+                                     hipStream_t stream)
 {
     if (N <= 0) return hipSuccess;
-    const uint32_t blocks = static_cast<uint32_t>((N + 255) / 256);
-    random_permutation_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(seed, t, N, perm);
+    const int64_t n_padded = sort_padded_count(N);
+    permutation_items_kernel<<<dim3(static_cast<uint32_t>((n_padded + 255) / 256)), dim3(256), 0, stream>>>(
+        seed, t, N, n_padded, items);
+    hipError_t e = launch_sort_items(items, n_padded, stream);
+    if (e != hipSuccess) return e;
+    permutation_extract_kernel<<<dim3(static_cast<uint32_t>((N + 255) / 256)), dim3(256), 0, stream>>>(items, N, perm);
     return hipGetLastError();
 }
 

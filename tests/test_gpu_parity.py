@@ -613,15 +613,43 @@ def test_partly_filled_grid(M, d, n_present, dtype, P, p):
 # averaging in random groups (the simplified scheme of Thm 3.2) and list-based rounds
 # --------------------------------------------------------------------------
 
-@pytest.mark.parametrize("N", [16, 100, 1024, 4096])
+@pytest.mark.parametrize("N", [16, 100, 1024, 4096, 6561, 16384])
 def test_random_permutation_bit_exact(N):
     # the permutation only depends on N: use any handle with that many peers
-    shapes = {16: (4, 2), 100: (10, 2), 1024: (32, 2), 4096: (16, 3)}
+    # (6561 and 16384 peers span several chunks of the device sort, the first with padding)
+    shapes = {16: (4, 2), 100: (10, 2), 1024: (32, 2), 4096: (16, 3), 6561: (3, 8), 16384: (4, 7)}
     M, d = shapes[N]
     with binding.Moshpit(N, 8, M, d, 0) as m:
         for t, seed in ((0, 1), (3, 2**63 + 5), (7, 12345)):
             say(f"perm N={N} t={t} seed={seed}")
             assert np.array_equal(m.random_permutation(t, seed), orc.random_permutation(seed, t, N))
+
+
+def _np_mix64(x):
+    x = x ^ (x >> np.uint64(32)); x = x * np.uint64(0x9E3779B97F4A7C15)
+    x = x ^ (x >> np.uint64(29)); x = x * np.uint64(0x6A09E667F3BCC909)
+    return x ^ (x >> np.uint64(32))
+
+
+@pytest.mark.parametrize("M,d", [(16, 4), (2, 18), (3, 11)])
+def test_random_permutation_of_many_peers(M, d):
+    """65,536 to 262,144 peers (the oracle's rank-by-counting would take minutes): the
+    permutation is the unique ascending order of the keys stated in the header, ties by
+    index; checked with the keys recomputed here in 64-bit numpy arithmetic."""
+    N = M ** d
+    with binding.Moshpit(N, 8, M, d, 0) as m:
+        for t, seed in ((2, 7), (9, 2**64 - 3)):
+            say(f"perm N={N} t={t} seed={seed}")
+            got = m.random_permutation(t, seed)
+            with np.errstate(over="ignore"):
+                rk = _np_mix64(np.uint64(seed) + np.uint64(0xD1B54A32D192ED03) * np.uint64(t + 1))
+                keys = _np_mix64(rk ^ np.arange(N, dtype=np.uint64))
+            assert np.array_equal(got, np.lexsort((np.arange(N), keys)).astype(np.int32))
+        small = orc.random_permutation(7, 2, 4096)          # the recomputed keys are the oracle's keys
+        with np.errstate(over="ignore"):
+            rk = _np_mix64(np.uint64(7) + np.uint64(0xD1B54A32D192ED03) * np.uint64(3))
+            keys = _np_mix64(rk ^ np.arange(4096, dtype=np.uint64))
+        assert np.array_equal(small, np.lexsort((np.arange(4096), keys)))
 
 
 @pytest.mark.parametrize("M,d,P,dtype,gs,p", [(32, 2, 3_000, 0, 32, 0.0), (32, 2, 1_001, 0, 7, 0.2),
@@ -956,13 +984,92 @@ def test_user_stream_and_two_handles():
     assert_state_close(to_f64(B), ref_b, TOL[1], "stream b")
 
 
+def test_host_masks_are_read_before_the_call_returns():
+    """A mask in PINNED host memory that the caller overwrites right after moshpit_round
+    returned, while earlier work still occupies the stream: the round must use the bytes
+    the mask held at the call (an asynchronous copy straight from pinned memory would
+    read the overwritten ones).  Same for an explicit schedule and the refresh masks."""
+    M, d, P = 16, 2, 200_000
+    N = M * M
+    w = inputs.Workload("pinned", N, M, d, P, 0, "peer_offset", 1, 0.3, 0, 4, 55, 56)
+    X = inputs.make_state(w, DEV)
+    ref = to_f64(X).copy()
+    masks = orc.schedule_masks(1, 0.3, 56, 0, N, 0, 4)
+    lib = binding.load_library()
+    pinned = torch.empty(4, N, dtype=torch.uint8).pin_memory()
+    with binding.Moshpit(N, P, M, d, 0) as m:
+        m.bind_state(X)
+        for rep in range(3):                                   # keep the stream busy
+            m.run(100 + 2 * rep, 2, None)
+        pinned[0].copy_(torch.from_numpy(masks[0]))
+        assert lib.moshpit_round(m._h, 0, pinned[0].data_ptr()) == 0
+        pinned[0].zero_()                                      # the caller reuses its buffer at once
+        pinned[:3].copy_(torch.from_numpy(masks[1:4]))
+        cs = binding._CSchedule(binding.SCHED_EXPLICIT, 0, 0.0, 0, pinned.data_ptr(), 0, 0)
+        import ctypes
+        assert lib.moshpit_run(m._h, 1, 3, ctypes.byref(cs), 0, None, None) == 0
+        pinned.zero_()
+        m.sync()
+    for rep in range(3):
+        orc.run(ref, M, d, 100 + 2 * rep, 2, None)
+    orc.run(ref, M, d, 0, 4, masks)
+    assert_state_close(to_f64(X), ref, TOL[0], "pinned masks")
+
+
+def test_rejoin_schedule_far_into_a_run():
+    """Die-and-rejoin masks a million rounds in, and their continuation from the state the
+    handle carries, equal the oracle's (which walks every round from 0)."""
+    N, M, d, down, p, seed, t0 = 256, 16, 2, 3, 0.2, 4321, 1_000_000
+    sched = binding.Schedule(kind=binding.SCHED_REJOIN, p=p, seed=seed, down_rounds=down)
+    want = orc.schedule_masks(2, p, seed, down, N, t0, 12)
+    with binding.Moshpit(N, 8, M, d, 0) as m:
+        assert np.array_equal(m.schedule_mask(sched, t0, 5), want[:5])          # walks from round 0 once
+        assert np.array_equal(m.schedule_mask(sched, t0 + 5, 4), want[5:9])     # goes on from the carried state
+        assert np.array_equal(m.schedule_mask(sched, t0 + 10, 2), want[10:12])  # skips a round: walks it
+        assert np.array_equal(m.schedule_mask(sched, t0 + 2, 3), want[2:5])     # earlier than the carried state
+        other = binding.Schedule(kind=binding.SCHED_REJOIN, p=p, seed=seed + 1, down_rounds=down)
+        assert np.array_equal(m.schedule_mask(other, 7, 3), orc.schedule_masks(2, p, seed + 1, down, N, 7, 3))
+        assert np.array_equal(m.schedule_mask(sched, 0, 6), orc.schedule_masks(2, p, seed, down, N, 0, 6))
+
+
+def test_first_launches_from_two_threads():
+    """Two host threads, each with a handle of its own, make the first launches of the
+    process's kernels at the same time (the per-device launch table is shared)."""
+    import threading
+    M, d, P, rounds = 32, 2, 4_096, 6
+    N = M * M
+    results = {}
+
+    def work(k):
+        w = inputs.Workload(f"thread-{k}", N, M, d, P, k % 2, "peer_offset", 1, 0.1, 0, rounds, 100 + k, 200 + k)
+        X = inputs.make_state(w, DEV)
+        ref = to_f64(X).copy()
+        stream = torch.cuda.Stream(device=DEV)
+        torch.cuda.synchronize()
+        with binding.Moshpit(N, P, M, d, w.dtype) as m:
+            m.bind_state(X, stream)
+            m.run(0, rounds, sched_of(w), flags=binding.RUN_FUSED if k >= 2 else 0)
+            m.sync()
+        orc.run(ref, M, d, 0, rounds, orc.schedule_masks(1, 0.1, 200 + k, 0, N, 0, rounds))
+        results[k] = (to_f64(X), ref, w.dtype)
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert sorted(results) == [0, 1, 2, 3]
+    for k, (got, ref, dtype) in results.items():
+        assert_state_close(got, ref, TOL[dtype], f"thread {k}")
+
+
 # --------------------------------------------------------------------------
 # Alg. 1 with chunk-index keys
 # --------------------------------------------------------------------------
 
 @pytest.mark.parametrize("M,d,P,dtype,p", [(32, 2, 1_000, 0, 0.05), (16, 3, 264, 1, 0.1), (4, 3, 3_001, 0, 0.3),
                                            (3, 4, 96, 0, 0.2), (2, 5, 512, 1, 0.0), (8, 1, 100, 0, 0.25),
-                                           (7, 2, 4_096, 0, 0.0)])
+                                           (7, 2, 4_096, 0, 0.0), (4, 7, 64, 0, 0.1), (3, 8, 24, 1, 0.2)])
 def test_dynamic_key_rounds(M, d, P, dtype, p):
     N, rounds, seed = M ** d, 2 * d + 2, 1234
     w = inputs.Workload("dynamic", N, M, d, P, dtype, "peer_offset", 1, p, 0, rounds, 91, 92)
