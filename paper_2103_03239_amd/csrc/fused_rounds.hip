@@ -18,25 +18,19 @@
 // Schedule.  Persistent blocks, 16 waves per compute unit: two blocks of 512
 // threads with 80 KiB of LDS each, or, when that lets more axes be fused, one
 // block of 1024 threads with 160 KiB.  A thread owns 8 tile slots of 16 bytes
-// (512 * 8 * 16 B = 64 KiB, or 128 KiB, of tile) and 8 registers of 16 bytes that
-// carry them between HBM and LDS.  Three tiles are in flight per block: tile k is
-// averaged in LDS; the results of tile k-1 sit in the slot registers and leave for
-// HBM slot by slot, and each register that has been stored is at once the target of
-// the 128-bit load of the same slot of tile k+1.  These stores and loads are issued
-// in portions, one portion before each of the first rounds of tile k, so the
-// memory pipeline sees a steady trickle (about the compute unit's share of HBM
-// bandwidth) instead of a burst: a wave that issues vector memory instructions
-// faster than they drain stalls at the issue stage, and the round barriers pass
-// that stall to the whole block.  After the last round every thread swaps its
-// slots: results of tile k from LDS into the registers, tile k+1 from the
-// registers into LDS.
+// (512 * 8 * 16 B = 64 KiB, or 128 KiB, of tile).  While the rounds of tile k
+// run in LDS the 128-bit loads of tile k+1 are in flight into registers;
+// afterwards every thread swaps its slots (tile k to HBM, tile k+1 into LDS)
+// and the stores drain during the rounds of tile k+1.  A wave that issues
+// vector memory instructions faster than the compute unit's share of HBM
+// delivers stalls at the issue stage, and the round barriers pass that stall to
+// the whole block; two blocks out of step with each other are what overlaps
+// memory time with arithmetic.
 //
 // LDS layout (dynamic): [tile: rows x Wb bytes][2 x bitmaps: rounds x groups
 // u64][byte offset of every local row][2 x row flags: rows bytes][tile offset of
 // the first row of every group per axis][pad][RN(1/k), k = 0..64][16 bytes of zeros][16 bytes
 // of write-only trash].
-#include <cstdlib>
-
 #include "moshpit_internal.h"
 
 namespace moshpit {
@@ -327,45 +321,31 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
     // having all of it hoisted into registers that live across the rounds.
     const int32_t slot_dq = kThreads / Wv, slot_dr = kThreads - slot_dq * Wv;
 
-    // Slots [b_lo, b_hi): store the slot registers that hold results of tile `out`
-    // (mask out_used) to HBM, then issue the 128-bit loads of the same slots of tile
-    // `in` into the same registers and add them to the mask in_used.  Loads and
-    // stores are asm statements so that the compiler does not track them: for a
-    // load of its own, issued in a loop into a register that an earlier iteration
-    // may have left pending, it waits for ALL memory traffic first, which would
-    // serialise every load behind the stores before it.  In exchange the wait is
-    // ours to place: nothing may read or copy pre[] between a load and the
+    // Issue the 128-bit loads of slots [b_lo, b_hi) of a tile into registers and
+    // add them to the mask of slots in use.  The load is written as an asm
+    // statement so that the compiler does not track it: for a load of its own,
+    // issued in a loop into a register that an earlier iteration may have left
+    // pending, it waits for ALL memory traffic first, which would serialise
+    // every load behind the stores of the previous tile.  In exchange the wait
+    // is ours to place: nothing may read or copy pre[] between fetch() and the
     // vmcnt(0) wait that precedes the swap (each pre[b] is an in-out operand, so
-    // the load lands in the register that holds the variable).  A store has read
-    // its data registers two idle states after it was issued, so the load that
-    // follows may target them.
+    // the load lands in the register that holds the variable).
     u32x4 pre[kPrefetch];
 #pragma unroll
     for (int b = 0; b < kPrefetch; ++b) pre[b] = u32x4{0u, 0u, 0u, 0u};
-    auto move = [&](bool have_out, const TileRef &out, uint32_t out_used, bool have_in, const TileRef &in, int in_buf,
-                    int b_lo, int b_hi, uint32_t &in_used) {
-        const uint8_t *flag = rowflag0 + in_buf * p.rows_padded;
-        const int32_t seg_vec = in.seg_bytes / 16;
-        const char *in_origin = X + in.base * p.row_bytes + in.col0_bytes;
-        char *out_origin = X + out.base * p.row_bytes + out.col0_bytes;
+    auto fetch = [&](const TileRef &t, int buf, int b_lo, int b_hi, uint32_t &used) {
+        const uint8_t *flag = rowflag0 + buf * p.rows_padded;
+        const int32_t seg_vec = t.seg_bytes / 16;
+        const char *origin = X + t.base * p.row_bytes + t.col0_bytes;
         int32_t t_ = tid;
         asm volatile("" : "+v"(t_));
         int32_t lr = t_ / Wv, v = t_ - lr * Wv;
 #pragma unroll
         for (int b = 0; b < kPrefetch; ++b) {
-            if (b >= b_lo && b < b_hi) {
-                if (have_out && (out_used & (1u << b))) {
-                    char *dst = out_origin + rowoff[lr] + v * 16;
-                    // the two idle states keep a vector instruction that reuses the data
-                    // registers from changing them while the store still reads them (the
-                    // compiler pads its own wide stores the same way, not asm statements)
-                    asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" : : "v"(dst), "v"(pre[b]));
-                }
-                if (have_in && lr < p.rows && v < seg_vec && flag[lr]) {
-                    const char *src = in_origin + rowoff[lr] + v * 16;
-                    asm volatile("global_load_dwordx4 %0, %1, off nt" : "+v"(pre[b]) : "v"(src));
-                    in_used |= 1u << b;
-                }
+            if (b >= b_lo && b < b_hi && lr < p.rows && v < seg_vec && flag[lr]) {
+                const char *src = origin + rowoff[lr] + v * 16;
+                asm volatile("global_load_dwordx4 %0, %1, off nt" : "+v"(pre[b]) : "v"(src));
+                used |= 1u << b;
             }
             v += slot_dr;
             lr += slot_dq;
@@ -374,9 +354,8 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
     };
 
     // The fused rounds of one tile, in LDS, with the bitmaps of buffer `buf`.
-    // before_round(r) runs ahead of round r (for r > 0: once the barrier of round
-    // r - 1 has been passed).
-    auto compute = [&](const TileRef &t, int buf, auto before_round) {
+    // after_round(r) runs once the barrier of round r has been passed.
+    auto compute = [&](const TileRef &t, int buf, auto after_round) {
         const uint64_t *bm = bitmaps0 + buf * bm_count;
         const int32_t cchunks = t.seg_bytes / (CV * static_cast<int32_t>(sizeof(elem_t)));
         // SPLIT adjacent lanes share one (group, column chunk) item and take
@@ -390,7 +369,6 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
         const int32_t g_first = it0 / cchunks, c_first = it0 - g_first * cchunks;
         const int32_t dg = kItemThreads / cchunks, dc = kItemThreads - dg * cchunks;
         for (int32_t r = 0; r < p.rounds; ++r) {
-            before_round(r);
             const int32_t lf = (p.local_axis0 + r) % p.F;
             int32_t Sl = 1;
             for (int q = 0; q < lf; ++q) Sl *= p.M;
@@ -532,14 +510,15 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
                 if (cc >= cchunks) { cc -= cchunks; gl += 1; }
             }
             lds_barrier();
+            after_round(r);
         }
     };
 
     // Software pipeline over the block's tiles k = 0, 1, 2, ...  While tile k is
-    // averaged in LDS, the slot registers first hold the results of tile k-1; in
-    // `spread` portions, one before each of the first rounds, each register is
-    // stored to HBM and becomes the target of the load of tile k+1.  After the last
-    // round the registers and LDS swap contents.
+    // averaged in LDS, the loads of tile k+1 are issued into `pre` (before the
+    // first round, or in `spread` portions after the first rounds).  Afterwards
+    // tile k leaves LDS for HBM and tile k+1 enters LDS from `pre`; the stores
+    // drain while tile k+1 is averaged.
     const int64_t stride = gridDim.x;
     int64_t w = blockIdx.x;
     if (w >= p.work_items) return;
@@ -547,7 +526,7 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
     int buf_cur = 0;
     prepare(cur, buf_cur);
     uint32_t used_cur = 0;
-    move(false, cur, 0u, true, cur, buf_cur, 0, kPrefetch, used_cur);
+    fetch(cur, buf_cur, 0, kPrefetch, used_cur);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
     for (int b = 0; b < kPrefetch; ++b) asm volatile("" : "+v"(pre[b]));
@@ -556,10 +535,6 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
         if (used_cur & (1u << b)) *reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(tid + b * kThreads) * 16) = pre[b];
     lds_barrier();
 
-    const int32_t spread = p.rounds < p.spread ? p.rounds : p.spread;      // >= 1
-    bool has_prev = false;
-    TileRef prev = cur;
-    uint32_t used_prev = 0;
     while (true) {
         const bool has_next = w + stride < p.work_items;
         TileRef nxt = cur;
@@ -570,11 +545,13 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
             buf_next = nxt.plane == cur.plane ? buf_cur : buf_cur ^ 1;
             prepare(nxt, buf_next);
         }
-        // slots [r * kPrefetch / spread, (r + 1) * kPrefetch / spread) before round r < spread
+        // spread == 0: all slots of tile k+1 before the first round; otherwise slots
+        // [r * kPrefetch / spread, (r + 1) * kPrefetch / spread) after round r < spread
+        const int32_t spread = p.rounds < p.spread ? p.rounds : p.spread;
+        if (has_next && p.spread == 0) fetch(nxt, buf_next, 0, kPrefetch, used_next);
         compute(cur, buf_cur, [&](int32_t r) {
-            if ((has_prev || has_next) && r < spread)
-                move(has_prev, prev, used_prev, has_next, nxt, buf_next, r * kPrefetch / spread,
-                     (r + 1) * kPrefetch / spread, used_next);
+            if (has_next && r < spread)
+                fetch(nxt, buf_next, r * kPrefetch / spread, (r + 1) * kPrefetch / spread, used_next);
         });
 
         // Wait for the loads of tile k+1 (and, in passing, for the stores of tile
@@ -582,34 +559,41 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
         for (int b = 0; b < kPrefetch; ++b) asm volatile("" : "+v"(pre[b]));
-        // Each thread owns the same tile slots for every tile, so it swaps tile k
-        // out of LDS into its registers and tile k+1 into LDS, slot by slot,
-        // without a barrier.
+        // Each thread owns the same tile slots for every tile, so it swaps tile
+        // k out of LDS and tile k+1 in, slot by slot, without a barrier.
+        constexpr int kHalf = kPrefetch / 2;
         {
+            char *origin = X + cur.base * p.row_bytes + cur.col0_bytes;
             int32_t t_ = tid;
             asm volatile("" : "+v"(t_));
+            int32_t lr = t_ / Wv, v = t_ - lr * Wv;
 #pragma unroll
-            for (int b = 0; b < kPrefetch; ++b) {
-                u32x4 *slot = reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(t_ + b * kThreads) * 16);
-                const u32x4 incoming = pre[b];
-                if (used_cur & (1u << b)) pre[b] = *slot;
-                if (used_next & (1u << b)) *slot = incoming;
+            for (int h = 0; h < 2; ++h) {
+                u32x4 val[kHalf];
+#pragma unroll
+                for (int q = 0; q < kHalf; ++q) {
+                    const int b = h * kHalf + q;
+                    u32x4 *slot = reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(t_ + b * kThreads) * 16);
+                    if (used_cur & (1u << b)) val[q] = *slot;
+                    if (used_next & (1u << b)) *slot = pre[b];
+                }
+#pragma unroll
+                for (int q = 0; q < kHalf; ++q) {
+                    const int b = h * kHalf + q;
+                    if (used_cur & (1u << b))
+                        __builtin_nontemporal_store(val[q], reinterpret_cast<u32x4 *>(origin + rowoff[lr] + v * 16));
+                    v += slot_dr;
+                    lr += slot_dq;
+                    if (v >= Wv) { v -= Wv; lr += 1; }
+                }
             }
         }
-        prev = cur;
-        used_prev = used_cur;
-        has_prev = true;
         if (!has_next) break;
         lds_barrier();
         w += stride;
         cur = nxt;
         used_cur = used_next;
         buf_cur = buf_next;
-    }
-    // the results of the block's last tile
-    {
-        uint32_t none = 0;
-        move(true, prev, used_prev, false, prev, buf_cur, 0, kPrefetch, none);
     }
 }
 
@@ -693,13 +677,11 @@ bool plan_with(int bpc, int dtype, int64_t N, int32_t M, int32_t d, int64_t P, i
     // single-round kernel, so a pass of only two rounds is slower than two single rounds
     // (measured: 10.6 ms against 9.0 ms on 16 GiB); from three rounds on the pass wins.
     if (bpc == 1 && rounds < 3) return false;
-    // In how many portions the stores of the previous tile and the loads of the next one
-    // are issued, one portion before each of the first rounds.
-    p.spread = rounds < kPrefetch ? rounds : kPrefetch;
-    if (const char *v = std::getenv("MOSHPIT_FUSED_SPREAD")) {
-        const int sp = std::atoi(v);
-        if (sp >= 1 && sp <= kPrefetch) p.spread = sp;
-    }
+    // When the loads of the next tile are issued (measured on MI355X): two blocks per
+    // compute unit do best issuing them all before the first round; a block that has the
+    // compute unit to itself issues them in 2 or 4 portions, one after each of the first
+    // rounds, once there are enough rounds to spread them over.
+    p.spread = bpc == 1 ? (rounds >= 7 ? 4 : rounds >= 5 ? 2 : 0) : 0;
     const int64_t fixed = fixed_lds(rounds, rows, p.groups, F);
     int64_t budget = kLdsBytes - fixed;                          // LDS left for the tile ...
     const int64_t reg_tile = static_cast<int64_t>(kThreads) * kPrefetch * 16;   // ... and what the prefetch registers hold
