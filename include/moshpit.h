@@ -291,15 +291,20 @@ int moshpit_grouped_round(moshpit_ctx *h, const int32_t *index_host, int64_t n_i
  * waves_per_cu = resident waves per compute unit, 1..32 (0 = default); the
  * kernel runs fastest when the row loads in flight on the whole chip stay
  * near 16-32 MiB, so groups with many rows want few resident waves.
- * Results never depend on nontemporal, block or waves_per_cu; they depend on
- * unroll only through the (documented, fixed) summation tree.
+ * order = how the (group, column tile) work items are dealt to the blocks:
+ * 0 = in order, column tiles fastest; 1 = each of the 8 dies of the GPU streams
+ * through an eighth of the list (steadier when the rows of a group are a few
+ * MiB apart, slower otherwise); -1 = chosen from the distance between the rows
+ * of a group.
+ * Results never depend on nontemporal, block, waves_per_cu or order; they
+ * depend on unroll only through the (documented, fixed) summation tree.
  *
  * moshpit_copy_probe queues a plain 128-bit copy of nbytes (multiple of 16,
  * both pointers device, 16-byte aligned) on hip_stream: the streaming ceiling
  * the averaging kernel is compared with, and the known-size kernel used to
  * calibrate HBM traffic counters. */
 int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t nontemporal, int32_t block,
-                       int32_t waves_per_cu);
+                       int32_t waves_per_cu, int32_t order);
 int moshpit_copy_probe(void *dst_dev, const void *src_dev, int64_t nbytes, void *hip_stream);
 
 /* Wait until everything queued on the bound stream has finished. */

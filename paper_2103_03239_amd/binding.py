@@ -81,7 +81,7 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_refresh.argtypes = [vp, i64, ctypes.c_uint64, vp, vp]
     lib.moshpit_refresh_donors.argtypes = [vp, i64, ctypes.c_uint64, vp, vp, vp]
     lib.moshpit_grouped_round.argtypes = [vp, vp, i64, i32, vp]
-    lib.moshpit_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32]
+    lib.moshpit_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32, i32]
     lib.moshpit_copy_probe.argtypes = [vp, vp, i64, vp]
     lib.moshpit_sync.argtypes = [vp]
     lib.moshpit_last_error.argtypes = [vp]
@@ -290,8 +290,8 @@ class Moshpit:
                     "grouped_round")
 
     def set_tuning(self, cols: int = 0, unroll: int = 0, nontemporal: int = -1, block: int = 0,
-                   waves_per_cu: int = 0) -> None:
-        self._check(self._lib.moshpit_set_tuning(self._h, cols, unroll, nontemporal, block, waves_per_cu),
+                   waves_per_cu: int = 0, order: int = -1) -> None:
+        self._check(self._lib.moshpit_set_tuning(self._h, cols, unroll, nontemporal, block, waves_per_cu, order),
                     "set_tuning")
 
     def sync(self) -> None:

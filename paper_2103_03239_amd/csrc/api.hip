@@ -262,7 +262,7 @@ int reserve_refresh(moshpit_ctx *h)
 
 // Draw the donors of round t from two device masks and, if asked, copy their rows.
 int queue_refresh(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *prev_dev, const uint8_t *cur_dev,
-                  bool copy)
+                  bool copy, int64_t expected_rows)
 {
     int rc = reserve_refresh(h);
     if (rc != MOSHPIT_OK) return rc;
@@ -270,7 +270,8 @@ int queue_refresh(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *prev_
     int32_t *counts = returning + h->N;
     HIP_TRY(h, launch_refresh_plan(prev_dev, cur_dev, h->N, seed, t, candidates, donor, returning, counts, h->stream));
     if (copy)
-        HIP_TRY(h, launch_refresh_copy(h->X, h->dtype, h->N, h->P, h->row_stride, donor, returning, counts, h->stream));
+        HIP_TRY(h, launch_refresh_copy(h->X, h->dtype, h->N, h->P, h->row_stride, donor, returning, counts, expected_rows,
+                                       h->stream));
     return MOSHPIT_OK;
 }
 
@@ -455,8 +456,12 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
                                               rounds - r, &plan);
         if (refresh && r > 0) {
             const uint8_t *presence = s->group_skip ? h->d_masks_raw : h->d_masks;
+            // peers that return per round: about p * N under the seeded schedules; unknown for explicit ones
+            const int64_t guess = s->kind == MOSHPIT_SCHED_EXPLICIT
+                                      ? h->N / 4
+                                      : static_cast<int64_t>(1.5 * s->p * static_cast<double>(h->N)) + 16;
             rc = queue_refresh(h, t0 + r, s->seed, presence + static_cast<int64_t>(r - 1) * h->N,
-                               presence + static_cast<int64_t>(r) * h->N, true);
+                               presence + static_cast<int64_t>(r) * h->N, true, guess);
             if (rc != MOSHPIT_OK) return rc;
         }
         if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * pass], h->stream));
@@ -745,7 +750,9 @@ int moshpit_refresh(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *ali
     if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
     rc = stage_refresh_masks(h, alive_prev_host, alive_cur_host);
     if (rc != MOSHPIT_OK) return rc;
-    return queue_refresh(h, t, seed, h->d_refresh_masks, h->d_refresh_masks + h->N, true);
+    int64_t returning = 0;                     // (the masks are on the host: count, to size the copy's launch)
+    for (int64_t i = 0; i < h->N; ++i) returning += (alive_cur_host[i] != 0 && alive_prev_host[i] == 0) ? 1 : 0;
+    return queue_refresh(h, t, seed, h->d_refresh_masks, h->d_refresh_masks + h->N, true, returning);
 }
 
 int moshpit_refresh_donors(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8_t *alive_prev_host,
@@ -756,7 +763,7 @@ int moshpit_refresh_donors(moshpit_ctx *h, int64_t t, uint64_t seed, const uint8
     if (!donors_host) return fail(h, MOSHPIT_EINVAL, "donors is NULL");
     int rc = stage_refresh_masks(h, alive_prev_host, alive_cur_host);
     if (rc != MOSHPIT_OK) return rc;
-    rc = queue_refresh(h, t, seed, h->d_refresh_masks, h->d_refresh_masks + h->N, false);
+    rc = queue_refresh(h, t, seed, h->d_refresh_masks, h->d_refresh_masks + h->N, false, 0);
     if (rc != MOSHPIT_OK) return rc;
     HIP_TRY(h, hipMemcpyAsync(donors_host, h->d_refresh + h->N, sizeof(int32_t) * static_cast<size_t>(h->N),
                               hipMemcpyDeviceToHost, h->stream));
@@ -821,7 +828,7 @@ int moshpit_sync(moshpit_ctx *h)
 }
 
 int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t nontemporal, int32_t block,
-                       int32_t waves_per_cu)
+                       int32_t waves_per_cu, int32_t order)
 {
     if (!h) return MOSHPIT_EINVAL;
     if (cols > 0 || unroll > 0) {
@@ -836,9 +843,11 @@ int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t non
     if (block != 0 && block != 64 && block != 128 && block != 256)
         return fail(h, MOSHPIT_EINVAL, "block must be 0, 64, 128 or 256");
     if (waves_per_cu < 0 || waves_per_cu > 32) return fail(h, MOSHPIT_EINVAL, "waves_per_cu must be in [0, 32]");
+    if (order < -1 || order > 1) return fail(h, MOSHPIT_EINVAL, "order must be -1, 0 or 1");
     h->tune.nt = nontemporal;
     h->tune.block = block;
     h->tune.waves_per_cu = waves_per_cu;
+    h->tune.order = order;
     return MOSHPIT_OK;
 }
 

@@ -18,8 +18,6 @@
 //
 // The participant bitmap of a group is built by the wave itself: lane j < M
 // reads alive[base + j*S] and a ballot gives a 64-bit mask (hence M <= 64).
-#include <cstdlib>
-
 #include "moshpit_internal.h"
 
 namespace moshpit {
@@ -136,18 +134,15 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
 
     for (int64_t w0 = blockIdx.x; w0 < work_items; w0 += gridDim.x) {
         int64_t w = w0;
-        if (order == 1) {            // blocks b, b+8, b+16, ... (one XCD) take consecutive work items
+        if (order == 1) {
+            // blocks b, b + 8, b + 16, ... (they run on the same one of the 8 dies) take
+            // consecutive work items: each die streams through an eighth of the list
             const int64_t per = (work_items + 7) >> 3;
             w = (w0 & 7) * per + (w0 >> 3);
-            if ((w0 >> 3) >= per || w >= work_items) continue;
+            if (w >= work_items) continue;
         }
-        int64_t g = w / tiles;
-        int64_t tile = w - g * tiles;
-        if (order == 2) {            // group-fastest
-            const int64_t groups = work_items / tiles;
-            tile = w / groups;
-            g = w - tile * groups;
-        }
+        const int64_t g = w / tiles;
+        const int64_t tile = w - g * tiles;
         int64_t base = 0;
         int32_t my_row = -1;                         // IDX: the row of position `lane`
         bool takes_part = false;
@@ -264,7 +259,7 @@ __global__ __launch_bounds__(kMaxBlock) void group_mean_kernel(char *X, int64_t 
 // share a compute unit, which bounds the number of row loads in flight.
 template <int DT, int VE, int COLS, int U, bool NT, bool IDX = false, bool SGD = false>
 hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *alive, const RoundGeom &geom,
-                      int block, int waves_per_cu, hipStream_t stream)
+                      int block, int waves_per_cu, int order, hipStream_t stream)
 {
     if (nvec <= 0) return hipSuccess;
     const int64_t per_tile = static_cast<int64_t>(block) * COLS;
@@ -273,9 +268,10 @@ hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *a
     const int64_t work = groups * tiles;
     if (work <= 0) return hipSuccess;
     int64_t grid = work < 0x7fffffffLL ? work : 0x7fffffffLL;
-    const int order = std::getenv("MOSHPIT_K1_ORDER") ? std::atoi(std::getenv("MOSHPIT_K1_ORDER")) : 0;
-    if (order == 1) grid = ((work + 7) >> 3) << 3;
-    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (order == 1) {
+        grid = ((work + 7) >> 3) << 3;
+        if (grid > 0x7fffffffLL) { grid = 0x7fffffffLL; order = 0; }    // (more work items than blocks: plain order)
+    }
     auto kernel = group_mean_kernel<DT, VE, COLS, U, NT, IDX, SGD>;
     size_t lds = 0;
     if (waves_per_cu > 0 && waves_per_cu < 32) {
@@ -294,28 +290,28 @@ hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *a
 
 template <int DT, int VE>
 hipError_t launch_shape(int cols, int unroll, bool nt, char *X, int64_t row_bytes, int64_t nvec,
-                        const uint8_t *alive, const RoundGeom &geom, int block, int wpc, hipStream_t stream)
+                        const uint8_t *alive, const RoundGeom &geom, int block, int wpc, int order, hipStream_t stream)
 {
     if (geom.index != nullptr) {
         // peer-list groups: the default shapes only, streaming accesses
-        if (cols == 1 && unroll == 16) return launch_one<DT, VE, 1, 16, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
-        if (cols == 2 && unroll == 8) return launch_one<DT, VE, 2, 8, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
-        if (cols == 4 && unroll == 4) return launch_one<DT, VE, 4, 4, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
-        if (cols == 4 && unroll == 2) return launch_one<DT, VE, 4, 2, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        if (cols == 1 && unroll == 16) return launch_one<DT, VE, 1, 16, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream);
+        if (cols == 2 && unroll == 8) return launch_one<DT, VE, 2, 8, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream);
+        if (cols == 4 && unroll == 4) return launch_one<DT, VE, 4, 4, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream);
+        if (cols == 4 && unroll == 2) return launch_one<DT, VE, 4, 2, true, true>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream);
         return hipErrorInvalidValue;
     }
     if (geom.grad != nullptr) {
         // Moshpit SGD step: the default shapes only, streaming accesses
-        if (cols == 1 && unroll == 16) return launch_one<DT, VE, 1, 16, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
-        if (cols == 2 && unroll == 8) return launch_one<DT, VE, 2, 8, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
-        if (cols == 4 && unroll == 4) return launch_one<DT, VE, 4, 4, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
-        if (cols == 4 && unroll == 2) return launch_one<DT, VE, 4, 2, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        if (cols == 1 && unroll == 16) return launch_one<DT, VE, 1, 16, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream);
+        if (cols == 2 && unroll == 8) return launch_one<DT, VE, 2, 8, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream);
+        if (cols == 4 && unroll == 4) return launch_one<DT, VE, 4, 4, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream);
+        if (cols == 4 && unroll == 2) return launch_one<DT, VE, 4, 2, true, false, true>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream);
         return hipErrorInvalidValue;
     }
 #define MOSHPIT_CASE(C, UU)                                                                          \
     if (cols == C && unroll == UU)                                                                   \
-        return nt ? launch_one<DT, VE, C, UU, true>(X, row_bytes, nvec, alive, geom, block, wpc, stream)   \
-                  : launch_one<DT, VE, C, UU, false>(X, row_bytes, nvec, alive, geom, block, wpc, stream);
+        return nt ? launch_one<DT, VE, C, UU, true>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream)   \
+                  : launch_one<DT, VE, C, UU, false>(X, row_bytes, nvec, alive, geom, block, wpc, order, stream);
     MOSHPIT_CASE(1, 4)
     MOSHPIT_CASE(1, 8)
     MOSHPIT_CASE(1, 16)
@@ -359,11 +355,33 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     }
     const bool nt = tune.nt != 0;
     const int block = (tune.block == 64 || tune.block == 128 || tune.block == 256) ? tune.block : 64;
+    // Block order (measured on MI355X over row sizes of 128 KiB .. 32 MiB, groups of 16 and of
+    // 32 rows).  Work items go to the blocks tile-fastest, so the waves in flight stream a
+    // handful of groups: up to 6.4 TB/s when the byte distance between the rows of a group
+    // spreads well over the memory channels, 4.3 - 5.4 TB/s when it is 4, 8 or 16 MiB with 16
+    // rows per group (2 MiB with 32).  For those distances each die is given an eighth of the
+    // work list to stream through (8 times as many row streams in flight): 5.7 - 5.8 TB/s
+    // whatever the distance, below the good cases of the plain order, above its bad ones.
+    int order = tune.order;
+    if (order < 0) {
+        order = 0;
+        if (geom.index == nullptr) {
+            const int64_t member_stride = geom.S * row_bytes;
+            const int64_t MiB = 1 << 20;
+            if (geom.M <= 16 ? (member_stride >= 4 * MiB && member_stride <= 16 * MiB)
+                             : (member_stride >= 2 * MiB && member_stride < 4 * MiB))
+                order = 1;
+        }
+    }
     int wpc = tune.waves_per_cu;
     if (wpc <= 0) {
         const int rows = geom.M < unroll ? geom.M : unroll;
         const int kib_per_wave = rows * cols * (block / 64) * (geom.grad != nullptr ? 2 : 1);
         wpc = (dtype == 0 ? 80 : 96) / kib_per_wave * (block / 64);
+        // groups of up to 16 rows (16 KiB in flight per wave): 6 waves; 8 when the rows of a
+        // group are less than 1 MiB apart or when every die streams its own part of the list
+        if (kib_per_wave == 16 && geom.M <= 16 && geom.grad == nullptr)
+            wpc = (order == 1 || geom.S * row_bytes < (1 << 20)) ? 8 : 6;
         if (wpc < 4) wpc = 4;
         if (wpc > 32) wpc = 32;
     }
@@ -371,8 +389,8 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     char *base = static_cast<char *>(X);
     hipError_t e = hipSuccess;
     if (nvec > 0) {
-        e = dtype == 0 ? launch_shape<0, 4>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, block, wpc, stream)
-                       : launch_shape<1, 8>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, block, wpc, stream);
+        e = dtype == 0 ? launch_shape<0, 4>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, block, wpc, order, stream)
+                       : launch_shape<1, 8>(cols, unroll, nt, base, row_bytes, nvec, alive, geom, block, wpc, order, stream);
         if (e != hipSuccess) return e;
     }
     if (tail0 < P) {
@@ -380,14 +398,14 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
         if (geom.grad != nullptr) {
             RoundGeom tg = geom;
             tg.grad = geom.grad + tail0 * esize;
-            e = dtype == 0 ? launch_one<0, 1, 1, 8, false, false, true>(tbase, row_bytes, P - tail0, alive, tg, 256, 32, stream)
-                           : launch_one<1, 1, 1, 8, false, false, true>(tbase, row_bytes, P - tail0, alive, tg, 256, 32, stream);
+            e = dtype == 0 ? launch_one<0, 1, 1, 8, false, false, true>(tbase, row_bytes, P - tail0, alive, tg, 256, 32, 0, stream)
+                           : launch_one<1, 1, 1, 8, false, false, true>(tbase, row_bytes, P - tail0, alive, tg, 256, 32, 0, stream);
         } else if (geom.index != nullptr)
-            e = dtype == 0 ? launch_one<0, 1, 1, 8, false, true>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream)
-                           : launch_one<1, 1, 1, 8, false, true>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream);
+            e = dtype == 0 ? launch_one<0, 1, 1, 8, false, true>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, 0, stream)
+                           : launch_one<1, 1, 1, 8, false, true>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, 0, stream);
         else
-            e = dtype == 0 ? launch_one<0, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream)
-                           : launch_one<1, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, stream);
+            e = dtype == 0 ? launch_one<0, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, 0, stream)
+                           : launch_one<1, 1, 1, 8, false>(tbase, row_bytes, P - tail0, alive, geom, 256, 32, 0, stream);
     }
     return e;
 }

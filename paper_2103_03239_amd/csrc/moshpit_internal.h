@@ -34,13 +34,16 @@ hipError_t launch_sort_items(SortItem *items, int64_t n_padded, hipStream_t stre
 // row, unroll = rows whose loads are issued before the first add, nt =
 // non-temporal loads and stores, block = threads per block (64/128/256),
 // waves_per_cu = resident waves per compute unit (enforced through the
-// launch's LDS reservation).  0 / -1 mean "choose from M and the dtype".
+// launch's LDS reservation), order = how work items are dealt to the blocks (0: in
+// order, column tiles fastest; 1: each of the 8 dies streams through an eighth of the
+// list).  0 / -1 mean "choose from the shape".
 struct MeanTuning {
     int cols = 0;
     int unroll = 0;
     int nt = -1;
     int block = 0;
     int waves_per_cu = 0;
+    int order = -1;
 };
 
 // Geometry of one round: group g (0 <= g < N/M) owns rows base(g) + j*S,
@@ -116,8 +119,10 @@ hipError_t launch_skip_filter(uint8_t *masks, int64_t N, int32_t M, int32_t d, i
 hipError_t launch_refresh_plan(const uint8_t *prev, const uint8_t *cur, int64_t N, uint64_t seed, int64_t t,
                                int32_t *candidates, int32_t *donor, int32_t *returning, int32_t *counts,
                                hipStream_t stream);
+// expected_rows: the host's guess of how many peers return (sizes the launch only).
 hipError_t launch_refresh_copy(void *X, int dtype, int64_t N, int64_t P, int64_t row_stride, const int32_t *donor,
-                               const int32_t *returning, const int32_t *counts, hipStream_t stream);
+                               const int32_t *returning, const int32_t *counts, int64_t expected_rows,
+                               hipStream_t stream);
 
 // Queue the random-permutation kernels: perm[r] = peer of rank r when the peers
 // are ordered by their 64-bit key of (seed, t), ties by index (device, N int32).

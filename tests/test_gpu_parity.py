@@ -227,22 +227,22 @@ def test_errors_are_reported_not_crashed():
         m.sync()
 
 
-@pytest.mark.parametrize("cols,unroll,nt,block,wpc", [
-    (1, 4, 0, 64, 4), (1, 8, 1, 64, 3), (1, 16, 0, 128, 2), (2, 2, 1, 256, 32), (2, 4, 0, 64, 1), (2, 8, 1, 128, 6),
-    (4, 2, 0, 256, 8), (4, 4, 1, 64, 6), (1, 8, 1, 256, 4), (1, 8, 0, 0, 0)])
-def test_every_launch_shape(cols, unroll, nt, block, wpc):
+@pytest.mark.parametrize("cols,unroll,nt,block,wpc,order", [
+    (1, 4, 0, 64, 4, 0), (1, 8, 1, 64, 3, 1), (1, 16, 0, 128, 2, -1), (2, 2, 1, 256, 32, 1), (2, 4, 0, 64, 1, 0),
+    (2, 8, 1, 128, 6, 1), (4, 2, 0, 256, 8, -1), (4, 4, 1, 64, 6, 1), (1, 8, 1, 256, 4, 0), (1, 8, 0, 0, 0, 1)])
+def test_every_launch_shape(cols, unroll, nt, block, wpc, order):
     """All launch shapes of the averaging kernel meet the same parity bar."""
     for dtype, M, d, P in ((0, 16, 2, 6_001), (1, 4, 3, 9_000)):
         N = M ** d
         w = inputs.Workload("shape", N, M, d, P, dtype, "normal", 1, 0.2, 0, 5, 5, 6)
-        say(f"shape cols={cols} unroll={unroll} nt={nt} block={block} wpc={wpc} dtype={dtype}")
+        say(f"shape cols={cols} unroll={unroll} nt={nt} block={block} wpc={wpc} order={order} dtype={dtype}")
         X = inputs.make_state(w, DEV, row_stride=P + (8 - P % 8) % 8)
         ref = to_f64(X).copy()
         masks = orc.schedule_masks(1, 0.2, 6, 0, N, 0, 5)
         orc.run(ref, M, d, 0, 5, masks)
         with binding.Moshpit(N, P, M, d, dtype) as m:
             m.bind_state(X)
-            m.set_tuning(cols, unroll, nt, block, wpc)
+            m.set_tuning(cols, unroll, nt, block, wpc, order)
             m.run(0, 5, sched_of(w))
             m.sync()
         assert_state_close(to_f64(X), ref, TOL[dtype], "launch shape")
