@@ -343,6 +343,16 @@ def measure_extras(m, X, w, all_masks, row_stride, dev):
     out["sgd_round"] = {"ms_per_round": round(sg_ms, 4), "gbps": round(sg_bytes / (sg_ms * 1e-3) / 1e9, 1),
                         "note": "theta <- group mean of (theta - gamma*g); includes the host-to-device copy of each round's mask"}
     log(f"[bench] Moshpit SGD round: {sg_ms:.3f} ms per round, {out['sgd_round']['gbps']} GB/s")
+    # a whole iteration of Moshpit SGD (local step + the workload's rounds): fused, the local step is
+    # applied while the first pass loads its tiles; round by round it rides on the first round's kernel
+    from paper_2103_03239_amd import binding
+    sched = binding.Schedule(kind=w.kind, p=w.p, seed=w.mask_seed, down_rounds=w.down)
+    m.sgd_run(0, w.rounds, G, 1e-3, sched, flags=binding.RUN_FUSED)
+    it_fused = timed(lambda r: m.sgd_run((r + 1) * w.rounds, w.rounds, G, 1e-3, sched, flags=binding.RUN_FUSED), 3)
+    it_plain = timed(lambda r: m.sgd_run((r + 4) * w.rounds, w.rounds, G, 1e-3, sched), 3)
+    out["sgd_iteration"] = {"rounds": w.rounds, "ms_fused": round(it_fused, 4), "ms_round_by_round": round(it_plain, 4),
+                            "note": "theta - gamma*g for the peers present in the first round, then the rounds"}
+    log(f"[bench] Moshpit SGD iteration with {w.rounds} rounds: {it_fused:.3f} ms fused, {it_plain:.3f} ms round by round")
     del G
 
     # returning peers copy an up-to-date peer's parameters (App. on a dynamic number of peers):
@@ -470,6 +480,7 @@ def main() -> int:
         "random_groups": head.get("random_groups"),
         "dynamic_keys": head.get("dynamic_keys"),
         "sgd_round": head.get("sgd_round"),
+        "sgd_iteration": head.get("sgd_iteration"),
         "refresh": head.get("refresh"),
         "cpu_baseline": head.get("cpu"),
         "workloads": workloads,

@@ -234,6 +234,24 @@ int moshpit_dynamic_keys(moshpit_ctx *h, int32_t *keys_host);
  * 3 * elem_size * P bytes per participating peer. */
 int moshpit_local_step(moshpit_ctx *h, const uint8_t *alive_host, const void *grad_dev,
                        int64_t grad_row_stride_elems, float gamma);
+
+/* An iteration of Moshpit SGD whose Moshpit All-Reduce takes several rounds
+ * (Alg. 2 with Alg. 1 inside; the paper's ALBERT setup runs two rounds per
+ * iteration on an 8 x 8 grid, Sec. 4.3): the peers that are present in round t0
+ * take their local step theta_i - gamma * g_i, then rounds t0 .. t0+rounds-1 run
+ * under schedule s exactly as in moshpit_run (same flags, same outputs; rounds
+ * >= 1; dist_out_host[0] is the distortion before the local step).  With
+ * MOSHPIT_RUN_FUSED, a gradient matrix laid out exactly like the state (same
+ * row stride, 16-byte aligned) and rounds that fuse, the local step is applied
+ * while the first pass loads its tiles: the iteration then moves 3 * elem_size
+ * * P bytes per participating peer and pass instead of 5.  There the stepped
+ * value is rounded to the storage type before it is averaged (for binary32
+ * state the result is bit-identical to moshpit_sgd_round followed by the
+ * remaining rounds; for bfloat16 it differs by that one extra rounding).
+ * Otherwise the first round runs as moshpit_sgd_round and the others follow. */
+int moshpit_sgd_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedule *s, int32_t flags,
+                    const void *grad_dev, int64_t grad_row_stride_elems, float gamma, double *dist_out_host,
+                    float *round_ms_out_host);
 int moshpit_sgd_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host, const void *grad_dev,
                       int64_t grad_row_stride_elems, float gamma);
 

@@ -23,7 +23,7 @@ RUN_DEFAULT, RUN_FUSED = 0, 1
 EXPORTS = [
     "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",
     "moshpit_run", "moshpit_dist_to_mean", "moshpit_dist_to_mean_static", "moshpit_dist_to_mean_subset", "moshpit_group_keys", "moshpit_schedule_mask",
-    "moshpit_dynamic_reset", "moshpit_dynamic_round", "moshpit_dynamic_keys", "moshpit_local_step", "moshpit_sgd_round", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_refresh", "moshpit_refresh_donors", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
+    "moshpit_dynamic_reset", "moshpit_dynamic_round", "moshpit_dynamic_keys", "moshpit_local_step", "moshpit_sgd_round", "moshpit_sgd_run", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_refresh", "moshpit_refresh_donors", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
 ]
 
 
@@ -76,6 +76,7 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_dynamic_keys.argtypes = [vp, vp]
     lib.moshpit_local_step.argtypes = [vp, vp, vp, i64, ctypes.c_float]
     lib.moshpit_sgd_round.argtypes = [vp, i64, vp, vp, i64, ctypes.c_float]
+    lib.moshpit_sgd_run.argtypes = [vp, i64, i32, ctypes.POINTER(_CSchedule), i32, vp, i64, ctypes.c_float, vp, vp]
     lib.moshpit_random_groups_round.argtypes = [vp, i64, ctypes.c_uint64, i32, vp]
     lib.moshpit_random_permutation.argtypes = [vp, i64, ctypes.c_uint64, vp]
     lib.moshpit_refresh.argtypes = [vp, i64, ctypes.c_uint64, vp, vp]
@@ -255,6 +256,19 @@ class Moshpit:
         keep, ptr = self._alive_ptr(alive)
         gp, gs = self._grad(G)
         self._check(self._lib.moshpit_sgd_round(self._h, t, ptr, gp, gs, gamma), "sgd_round")
+
+    def sgd_run(self, t0: int, rounds: int, G, gamma: float, schedule: Schedule | None = None, want_dist: bool = False,
+                want_times: bool = False, flags: int = 0):
+        cs, keep = _c_schedule(schedule, rounds, self.N)
+        gp, gs = self._grad(G)
+        dist = np.zeros(rounds + 1, dtype=np.float64) if want_dist else None
+        ms = np.zeros(rounds, dtype=np.float32) if want_times else None
+        rc = self._lib.moshpit_sgd_run(self._h, t0, rounds, ctypes.byref(cs) if cs is not None else None, flags, gp, gs,
+                                       gamma, dist.ctypes.data if want_dist else None,
+                                       ms.ctypes.data if want_times else None)
+        self._check(rc, "sgd_run")
+        del keep
+        return dist, ms
 
     def random_groups_round(self, t: int, seed: int, group_size: int, alive=None) -> None:
         keep, ptr = self._alive_ptr(alive)

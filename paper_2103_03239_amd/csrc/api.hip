@@ -416,8 +416,12 @@ int moshpit_round_dev(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev)
     return queue_round(h, t, alive_dev);
 }
 
-int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedule *s, int32_t flags,
-                double *dist_out_host, float *round_ms_out_host)
+namespace {
+// Rounds t0 .. t0+rounds-1 under schedule s.  grad != nullptr: an iteration of Moshpit SGD -
+// the peers present in round t0 first take their local step theta - gamma * g (fused into
+// the first pass over the state).
+int run_impl(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedule *s, int32_t flags,
+             double *dist_out_host, float *round_ms_out_host, const void *grad, int64_t grad_row_stride, float gamma)
 {
     int rc = check_ready(h);
     if (rc != MOSHPIT_OK) return rc;
@@ -452,8 +456,10 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
         const size_t pass = pass_rounds.size();
         const uint8_t *mask_r = failures ? h->d_masks + static_cast<int64_t>(r) * h->N : nullptr;
         FusedPlan plan;
-        const bool fuse = fused && plan_fused(h->dtype, h->N, h->M, h->d, h->P, h->row_stride, h->X, t0 + r,
-                                              rounds - r, &plan);
+        const bool step_now = grad != nullptr && r == 0;       // the local step rides on the first pass
+        const bool grad_fits = !step_now || (grad_row_stride == h->row_stride && reinterpret_cast<uintptr_t>(grad) % 16 == 0);
+        const bool fuse = fused && grad_fits && plan_fused(h->dtype, h->N, h->M, h->d, h->P, h->row_stride, h->X, t0 + r,
+                                                           rounds - r, &plan);
         if (refresh && r > 0) {
             const uint8_t *presence = s->group_skip ? h->d_masks_raw : h->d_masks;
             // peers that return per round: about p * N under the seeded schedules; unknown for explicit ones
@@ -467,8 +473,16 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
         if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * pass], h->stream));
         int32_t done = 1;
         if (fuse) {
+            plan.grad = step_now ? static_cast<const char *>(grad) : nullptr;
+            plan.gamma = gamma;
             HIP_TRY(h, launch_fused_rounds(h->X, h->dtype, plan, mask_r, h->stream));
             done = plan.rounds;
+        } else if (step_now) {
+            RoundGeom geom{h->N, h->M, axis_stride(h, t0 + r)};
+            geom.grad = static_cast<const char *>(grad);
+            geom.grad_row_bytes = grad_row_stride * (h->dtype == MOSHPIT_F32 ? 4 : 2);
+            geom.gamma = gamma;
+            HIP_TRY(h, launch_group_mean(h->X, h->dtype, h->P, h->row_stride, geom, mask_r, h->tune, h->stream));
         } else {
             rc = queue_round(h, t0 + r, mask_r);
             if (rc != MOSHPIT_OK) return rc;
@@ -502,6 +516,13 @@ int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedu
         }
     }
     return MOSHPIT_OK;
+}
+}  // namespace
+
+int moshpit_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedule *s, int32_t flags,
+                double *dist_out_host, float *round_ms_out_host)
+{
+    return run_impl(h, t0, rounds, s, flags, dist_out_host, round_ms_out_host, nullptr, 0, 0.f);
 }
 
 int moshpit_dist_to_mean(moshpit_ctx *h, double *out_host)
@@ -622,6 +643,18 @@ int moshpit_sgd_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host, cons
     geom.gamma = gamma;
     HIP_TRY(h, launch_group_mean(h->X, h->dtype, h->P, h->row_stride, geom, alive_dev, h->tune, h->stream));
     return MOSHPIT_OK;
+}
+
+int moshpit_sgd_run(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedule *s, int32_t flags,
+                    const void *grad_dev, int64_t grad_row_stride_elems, float gamma, double *dist_out_host,
+                    float *round_ms_out_host)
+{
+    int rc = check_ready(h);
+    if (rc != MOSHPIT_OK) return rc;
+    if (rounds < 1) return fail(h, MOSHPIT_EINVAL, "an iteration with averaging needs at least one round");
+    rc = check_grad(h, grad_dev, grad_row_stride_elems);
+    if (rc != MOSHPIT_OK) return rc;
+    return run_impl(h, t0, rounds, s, flags, dist_out_host, round_ms_out_host, grad_dev, grad_row_stride_elems, gamma);
 }
 
 int moshpit_local_step(moshpit_ctx *h, const uint8_t *alive_host, const void *grad_dev,

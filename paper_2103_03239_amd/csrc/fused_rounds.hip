@@ -28,7 +28,8 @@
 // memory time with arithmetic.
 //
 // LDS layout (dynamic): [tile: rows x Wb bytes][2 x bitmaps: rounds x groups
-// u64][byte offset of every local row][2 x row flags: rows bytes][tile offset of
+// u64][byte offset of every local row][2 x row flags: rows bytes][2 x local-step
+// flags: rows bytes][tile offset of
 // the first row of every group per axis][pad][RN(1/k), k = 0..64][16 bytes of zeros][16 bytes
 // of write-only trash].
 #include "moshpit_internal.h"
@@ -154,6 +155,29 @@ template <> struct Cols<1, 1> {
     }
 };
 
+// One 16-byte tile slot (4 binary32 or 8 bfloat16 values) after a local step of
+// Moshpit SGD (Alg. 2): x - gamma * g, formed in binary32 with one fused multiply-add
+// per value and rounded to the storage type.
+template <int DT> __device__ __forceinline__ u32x4 local_step(const u32x4 &x, const u32x4 &g, float gamma)
+{
+    if constexpr (DT == 0) {
+        u32x4 out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            out[e] = __float_as_uint(__fmaf_rn(-gamma, __uint_as_float(g[e]), __uint_as_float(x[e])));
+        return out;
+    } else {
+        u32x4 out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float lo = __fmaf_rn(-gamma, __uint_as_float(g[e] << 16), __uint_as_float(x[e] << 16));
+            const float hi = __fmaf_rn(-gamma, __uint_as_float(g[e] & 0xffff0000u), __uint_as_float(x[e] & 0xffff0000u));
+            out[e] = bf16_bits_rne(lo) | (bf16_bits_rne(hi) << 16);
+        }
+        return out;
+    }
+}
+
 // global row of local row lr: base + sum_f digit_f(lr) * gstride[f]
 __device__ __forceinline__ int64_t global_row(const FusedPlan &p, int64_t base, int32_t lr)
 {
@@ -247,7 +271,8 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
     uint64_t *bitmaps0 = reinterpret_cast<uint64_t *>(lds + p.tile_bytes);
     int64_t *rowoff = reinterpret_cast<int64_t *>(bitmaps0 + 2 * bm_count);      // byte offset of local row lr
     uint8_t *rowflag0 = reinterpret_cast<uint8_t *>(rowoff + p.rows_padded);
-    int32_t *lbase_tab = reinterpret_cast<int32_t *>(rowflag0 + 2 * p.rows_padded);
+    uint8_t *rowstep0 = rowflag0 + 2 * p.rows_padded;             // rows that take the local step (SGD pass)
+    int32_t *lbase_tab = reinterpret_cast<int32_t *>(rowstep0 + 2 * p.rows_padded);
     float *rcp_tab = reinterpret_cast<float *>(lds + p.lds_bytes - 32 - kRcpBytes);  // RN(1 / k), k = 0..64
     elem_t *zeros = reinterpret_cast<elem_t *>(lds + p.lds_bytes - 32);            // 16 bytes that hold 0
     elem_t *trash = reinterpret_cast<elem_t *>(lds + p.lds_bytes - 16);            // 16 bytes nobody reads
@@ -279,8 +304,9 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
         if (buf == 0) tag0 = t.plane; else tag1 = t.plane;
         unsigned long long *bm = reinterpret_cast<unsigned long long *>(bitmaps0 + buf * bm_count);
         uint8_t *flag = rowflag0 + buf * p.rows_padded;
+        uint8_t *step = rowstep0 + buf * p.rows_padded;
         for (int32_t i = tid; i < bm_count; i += kThreads) bm[i] = 0ull;
-        for (int32_t lr = tid; lr < p.rows; lr += kThreads) flag[lr] = 0;
+        for (int32_t lr = tid; lr < p.rows; lr += kThreads) { flag[lr] = 0; step[lr] = 0; }
         lds_barrier();
         const int32_t pairs = p.rounds * p.rows;
         constexpr int kB = 8;
@@ -309,6 +335,7 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
                     const int32_t gl = (lr / (Sl * p.M)) * Sl + lr % Sl;
                     atomicOr(&bm[r * p.groups + gl], 1ull << j);
                     flag[lr] = 1;                      // benign race: every writer stores 1
+                    if (r == 0) step[lr] = 1;          // (one writer: the thread of (round 0, lr))
                 }
             }
         }
@@ -533,6 +560,26 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
     for (int b = 0; b < kPrefetch; ++b)
         if (used_cur & (1u << b)) *reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(tid + b * kThreads) * 16) = pre[b];
+    // Moshpit SGD pass: the rows that are present in the pass's first round take their local
+    // step on the way in.  A thread rewrites its own tile slots only, so no barrier is needed
+    // between the tile's arrival in LDS and this.  (First tile of the block: gradient loads not
+    // overlapped with anything.)
+    if (p.grad != nullptr) {
+        const uint8_t *step = rowstep0 + buf_cur * p.rows_padded;
+        const char *g_origin = p.grad + cur.base * p.row_bytes + cur.col0_bytes;
+        int32_t lr = tid / Wv, v = tid - lr * Wv;
+#pragma unroll
+        for (int b = 0; b < kPrefetch; ++b) {
+            if ((used_cur & (1u << b)) && step[lr]) {
+                u32x4 *slot = reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(tid + b * kThreads) * 16);
+                const u32x4 g = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(g_origin + rowoff[lr] + v * 16));
+                *slot = local_step<DT>(*slot, g, p.gamma);
+            }
+            v += slot_dr;
+            lr += slot_dq;
+            if (v >= Wv) { v -= Wv; lr += 1; }
+        }
+    }
     lds_barrier();
 
     while (true) {
@@ -588,6 +635,39 @@ __global__ __launch_bounds__(threads_of(BPC)) __attribute__((amdgpu_waves_per_eu
                 }
             }
         }
+        // Moshpit SGD pass: the rows of the incoming tile that are present in the pass's first
+        // round take their local step, two slots at a time (few registers are free here): the
+        // gradients are requested, waited for, and the slots rewritten in LDS by their owner.
+        if (p.grad != nullptr && has_next) {
+            const uint8_t *step = rowstep0 + buf_next * p.rows_padded;
+            const char *g_origin = p.grad + nxt.base * p.row_bytes + nxt.col0_bytes;
+            int32_t t_ = tid;
+            asm volatile("" : "+v"(t_));
+            int32_t lr = t_ / Wv, v = t_ - lr * Wv;
+            constexpr int kBatch = 2;
+#pragma unroll
+            for (int b0 = 0; b0 < kPrefetch; b0 += kBatch) {
+                u32x4 grad[kBatch];
+                uint32_t stepping = 0;
+#pragma unroll
+                for (int q = 0; q < kBatch; ++q) {
+                    if ((used_next & (1u << (b0 + q))) && step[lr]) {
+                        grad[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(g_origin + rowoff[lr] + v * 16));
+                        stepping |= 1u << q;
+                    }
+                    v += slot_dr;
+                    lr += slot_dq;
+                    if (v >= Wv) { v -= Wv; lr += 1; }
+                }
+#pragma unroll
+                for (int q = 0; q < kBatch; ++q) {
+                    if (stepping & (1u << q)) {
+                        u32x4 *slot = reinterpret_cast<u32x4 *>(tile + static_cast<int64_t>(t_ + (b0 + q) * kThreads) * 16);
+                        *slot = local_step<DT>(*slot, grad[q], p.gamma);
+                    }
+                }
+            }
+        }
         if (!has_next) break;
         lds_barrier();
         w += stride;
@@ -603,7 +683,7 @@ int64_t fixed_lds(int64_t rounds, int64_t rows, int64_t groups, int64_t F)
 {
     const int64_t rows_padded = (rows + 15) / 16 * 16;
     // tables, slack, then (16-byte aligned) the reciprocals, 16 bytes of zeros, 16 bytes of write-only trash
-    return (2 * rounds * groups * 8 + rows_padded * 8 + 2 * rows_padded + F * groups * 4 + 32 + 15) / 16 * 16 +
+    return (2 * rounds * groups * 8 + rows_padded * 8 + 4 * rows_padded + F * groups * 4 + 32 + 15) / 16 * 16 +
            kRcpBytes + 32;
 }
 

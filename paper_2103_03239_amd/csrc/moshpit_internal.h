@@ -149,6 +149,11 @@ struct FusedPlan {
     int32_t Wb, tile_bytes, lds_bytes;
     int64_t row_bytes, row_valid_bytes;
     int64_t tiles, planes, work_items;
+    // Moshpit SGD pass (Alg. 2): rows present in the pass's first round enter the tile as
+    // theta - gamma * g, g read from `grad` (device, laid out exactly like the state: same
+    // row stride); nullptr = a plain pass
+    const char *grad;
+    float gamma;
     int64_t gstride[kFusedMaxAxes];   // global row stride of tile-local axis f
     int64_t ostride[40];              // global row strides of the outer axes
 };

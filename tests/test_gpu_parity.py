@@ -892,6 +892,60 @@ def test_sgd_iterations(M, d, P, dtype, p, pad):
         assert_state_close(to_f64(X), ref, TOL[dtype], w.name)
 
 
+@pytest.mark.parametrize("M,d,P,dtype,p,pad,gpad,t0,rounds", [
+    (8, 2, 4_096, 0, 0.1, 0, 0, 0, 2),        # the paper's ALBERT shape: two rounds per iteration on an 8 x 8 grid
+    (8, 2, 4_096, 1, 0.1, 0, 0, 0, 2),
+    (16, 2, 5_000, 0, 0.05, 0, 0, 1, 5),      # ragged last column tile, start on the second axis
+    (32, 2, 4_100, 0, 0.2, 0, 0, 0, 8),       # 1024 rows x 128-byte segments, one block per compute unit
+    (16, 3, 2_056, 1, 0.1, 0, 0, 0, 6),       # planes: the local step rides on the first of three passes
+    (4, 3, 9_999, 0, 0.1, 1, 1, 0, 6),        # rows not 16-byte aligned: nothing fuses
+    (4, 3, 10_000, 0, 0.0, 0, 8, 0, 3),       # gradient matrix with another row stride: first round unfused
+    (3, 3, 780, 0, 0.25, 0, 0, 2, 4),
+    (64, 1, 2_048, 0, 0.1, 0, 0, 0, 1),       # one axis, one round
+])
+def test_sgd_run(M, d, P, dtype, p, pad, gpad, t0, rounds):
+    """An iteration of Moshpit SGD with several averaging rounds: local step of the peers present in
+    the first round, then the rounds - against the oracle taking the same steps, through the fused
+    and the round-by-round path; for binary32 state both give the bits of moshpit_sgd_round followed
+    by the remaining rounds."""
+    N, gamma = M ** d, 0.05
+    w = inputs.Workload("sgd-run", N, M, d, P, dtype, "peer_offset", inputs.KIND_IID if p > 0 else inputs.KIND_NONE, p, 0,
+                        rounds, 161 + P, 162 + M)
+    say(f"sgd run {w} pad={pad} gpad={gpad} t0={t0}")
+    X0 = inputs.make_state(w, DEV, row_stride=P + pad)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(163)
+    G = torch.randn(N, P + gpad, generator=gen, device=DEV).to(w.torch_dtype)[:, :P]
+    masks = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, N, t0, rounds)
+    ref = to_f64(X0).copy()
+    d0 = orc.dist_to_mean(ref)
+    orc.local_step(ref, to_f64(G).copy(), np.float32(gamma), masks[0] if p > 0 else None)
+    dist_ref = orc.run(ref, M, d, t0, rounds, masks, want_dist=True)
+    dist_ref[0] = d0
+    results = []
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        for flags in (0, binding.RUN_FUSED):
+            X = inputs.make_state(w, DEV, row_stride=P + pad)
+            m.bind_state(X)
+            dist, _ = m.sgd_run(t0, rounds, G, gamma, sched_of(w), want_dist=True, flags=flags)
+            assert_state_close(to_f64(X), ref, TOL[dtype], f"{w.name} flags={flags}")
+            have = ~np.isnan(dist)
+            assert have[0] and have[-1]
+            assert_dist_close(dist[have], dist_ref[have], TOL[dtype], dist_floor(P, dtype, 1.5), w.name)
+            results.append(X)
+        Y = inputs.make_state(w, DEV, row_stride=P + pad)
+        m.bind_state(Y)
+        m.sgd_round(t0, G, gamma, masks[0] if p > 0 else None)
+        if rounds > 1:
+            m.run(t0 + 1, rounds - 1, sched_of(w))
+        m.sync()
+        assert torch.equal(results[0], Y), "round-by-round sgd_run differs from sgd_round + run"
+        if dtype == 0:
+            assert torch.equal(results[1], Y), "fused sgd_run differs from sgd_round + run"
+        with pytest.raises(binding.MoshpitError):
+            m.sgd_run(t0, 0, G, gamma)
+
+
 def test_sgd_quadratic_mean_trajectory():
     """Exact gradients of 1/2 ||theta - theta*||^2, all peers present: the mean
     over peers follows theta* + (1-gamma)^K (mean_0 - theta*) whatever the
