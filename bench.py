@@ -115,7 +115,8 @@ def measure(cfg: int, steps: int, warmup: int, cpu_cols: int, cpu_budget_s: floa
     t_gen = time.time()
     # rows start on 128-byte boundaries (only workload 3 needs padding for that: 24 elements)
     row_stride = inputs.aligned_row_stride(w.P, w.dtype) + row_pad
-    X = inputs.make_state(w, dev, row_stride=row_stride)
+    X = inputs.make_state(w, dev, row_stride=row_stride,
+                          progress=lambda done, n: log(f"[bench] state rows {done}/{n}") if n > 1024 else None)
     torch.cuda.synchronize()
     log(f"[bench] state generated in {time.time() - t_gen:.1f}s")
     stream = torch.cuda.current_stream(dev)

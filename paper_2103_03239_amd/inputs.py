@@ -67,12 +67,15 @@ def aligned_row_stride(P: int, dtype: int) -> int:
     return -(-P // per_line) * per_line
 
 
-def make_state(w: Workload, device: str | torch.device = "cpu", row_stride: int | None = None) -> torch.Tensor:
+def make_state(w: Workload, device: str | torch.device = "cpu", row_stride: int | None = None,
+               progress=None) -> torch.Tensor:
     """Draw the [N, P] peer-state matrix of a workload in its storage dtype.
 
     Rows are filled one at a time so no temporary larger than a row exists.
     With ``row_stride`` > P the result is a view into a padded [N, row_stride]
     buffer (padding filled with a sentinel the kernels must never touch).
+    ``progress(rows_done, N)``, if given, is called every 512 rows (a run under a
+    profiler that serialises launches spends minutes here).
     """
     device = torch.device(device)
     gen = torch.Generator(device=device)
@@ -97,4 +100,6 @@ def make_state(w: Workload, device: str | torch.device = "cpu", row_stride: int 
         elif w.init != "normal":
             raise ValueError(f"unknown init {w.init!r}")
         X[i].copy_(row)          # fp32 -> storage dtype, round-to-nearest-even
+        if progress is not None and (i + 1) % 512 == 0:
+            progress(i + 1, w.N)
     return X
