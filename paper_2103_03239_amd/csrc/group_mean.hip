@@ -350,7 +350,12 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     if (cols <= 0 || unroll <= 0 || geom.index != nullptr || geom.grad != nullptr) {
         if (geom.M > 8) { unroll = 16; cols = 1; }
         else if (geom.M > 4) { unroll = 8; cols = 2; }
-        else if (geom.M > 2) { unroll = 4; cols = 4; }
+        else if (geom.M > 2) {
+            // four rows per group: one vector per row and lane and 20 resident waves measured 2 %
+            // above four vectors and 5 waves on 100 MB rows (peer lists and the SGD step keep four)
+            unroll = 4;
+            cols = (geom.index != nullptr || geom.grad != nullptr) ? 4 : 1;
+        }
         else { unroll = 2; cols = 4; }
     }
     const bool nt = tune.nt != 0;
@@ -378,10 +383,14 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
         const int rows = geom.M < unroll ? geom.M : unroll;
         const int kib_per_wave = rows * cols * (block / 64) * (geom.grad != nullptr ? 2 : 1);
         wpc = (dtype == 0 ? 80 : 96) / kib_per_wave * (block / 64);
-        // groups of up to 16 rows (16 KiB in flight per wave): 6 waves; 8 when the rows of a
-        // group are less than 1 MiB apart or when every die streams its own part of the list
-        if (kib_per_wave == 16 && geom.M <= 16 && geom.grad == nullptr)
-            wpc = (order == 1 || geom.S * row_bytes < (1 << 20)) ? 8 : 6;
+        // groups of up to 16 rows (16 KiB in flight per wave): 6 waves; 8 when the rows are
+        // shorter than 1 MiB or when every die streams its own part of the list; 7 for groups
+        // given as a peer list; 6 for the Moshpit SGD step (which also streams the gradients)
+        if (rows * cols == 16 && geom.M <= 16) {
+            if (geom.grad != nullptr) wpc = 6;
+            else if (geom.index != nullptr) wpc = 7;
+            else wpc = (order == 1 || row_bytes < (1 << 20)) ? 8 : 6;
+        }
         if (wpc < 4) wpc = 4;
         if (wpc > 32) wpc = 32;
     }
