@@ -572,6 +572,35 @@ def test_fused_full_size_matches_single_rounds(cfg):
     assert torch.equal(A, B)
 
 
+@pytest.mark.parametrize("M,d,P,dtype,p,t0,rounds", [
+    (2, 14, 40, 0, 0.1, 12, 3),          # 16,384 peers in groups of 2, axes 12, 13, 0
+    (16, 4, 24, 0, 0.1, 2, 3),           # 65,536 peers: planes of 256 rows, rows of 96 bytes, axes 2, 3, 0
+    (64, 3, 8, 1, 0.05, 1, 2),           # 262,144 peers in groups of 64, one 16-byte vector per row
+])
+def test_many_peers_single_and_fused(M, d, P, dtype, p, t0, rounds):
+    """Grids of 16,384 to 262,144 peers with short rows (row index arithmetic far beyond
+    the workloads' 4,096 rows; the oracle scans all peers per group, which bounds the sizes):
+    whole state against the oracle, fused run bit-identical."""
+    N = M ** d
+    w = inputs.Workload(f"many-{M}-{d}", N, M, d, P, dtype, "normal", inputs.KIND_IID, p, 0, rounds, 31 + M, 32 + d)
+    say(f"case {w} t0={t0}")
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(w.data_seed)
+    A = torch.randn(N, P, generator=gen, device=DEV, dtype=torch.float32).to(w.torch_dtype)
+    B = A.clone()
+    ref = to_f64(A).copy()
+    masks = orc.schedule_masks(w.kind, w.p, w.mask_seed, w.down, N, t0, rounds)
+    orc.run(ref, M, d, t0, rounds, masks)
+    with binding.Moshpit(N, P, M, d, dtype) as m:
+        m.bind_state(A)
+        m.run(t0, rounds, sched_of(w))
+        m.bind_state(B)
+        m.run(t0, rounds, sched_of(w), flags=binding.RUN_FUSED)
+        m.sync()
+    assert torch.equal(A, B), "fused run differs from single rounds"
+    assert_state_close(to_f64(A), ref, TOL[dtype], w.name)
+
+
 # --------------------------------------------------------------------------
 # partly filled grids (N peers on a subset of the M^d vertices)
 # --------------------------------------------------------------------------
