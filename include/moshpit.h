@@ -325,6 +325,17 @@ int moshpit_set_tuning(moshpit_ctx *h, int32_t cols, int32_t unroll, int32_t non
                        int32_t waves_per_cu, int32_t order);
 int moshpit_copy_probe(void *dst_dev, const void *src_dev, int64_t nbytes, void *hip_stream);
 
+/* bfloat16 states are rounded to nearest, ties to even, after every round (the
+ * paper's experiments run in binary32; bfloat16 storage with binary32 sums is
+ * this library's option).  The kernels round with the hardware conversion of
+ * gfx950; this call runs both that conversion and its definition in integer
+ * arithmetic (add 0x7fff plus the lowest kept bit, keep the upper 16 bits; a NaN
+ * stays a quiet NaN) over all 2^32 binary32 bit patterns on hip_stream, waits,
+ * and writes the number of inputs on which they differ to *mismatches_out_host
+ * (host; expected 0).  About 10 ms.  Allocates 8 bytes of device memory for the
+ * duration of the call. */
+int moshpit_check_bf16_rounding(void *hip_stream, uint64_t *mismatches_out_host);
+
 /* Wait until everything queued on the bound stream has finished. */
 int moshpit_sync(moshpit_ctx *h);
 

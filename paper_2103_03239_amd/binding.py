@@ -23,7 +23,7 @@ RUN_DEFAULT, RUN_FUSED = 0, 1
 EXPORTS = [
     "moshpit_create", "moshpit_destroy", "moshpit_bind_state", "moshpit_round", "moshpit_round_dev",
     "moshpit_run", "moshpit_dist_to_mean", "moshpit_dist_to_mean_static", "moshpit_dist_to_mean_subset", "moshpit_group_keys", "moshpit_schedule_mask",
-    "moshpit_dynamic_reset", "moshpit_dynamic_round", "moshpit_dynamic_keys", "moshpit_local_step", "moshpit_sgd_round", "moshpit_sgd_run", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_refresh", "moshpit_refresh_donors", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_sync", "moshpit_last_error",
+    "moshpit_dynamic_reset", "moshpit_dynamic_round", "moshpit_dynamic_keys", "moshpit_local_step", "moshpit_sgd_round", "moshpit_sgd_run", "moshpit_random_groups_round", "moshpit_random_permutation", "moshpit_refresh", "moshpit_refresh_donors", "moshpit_grouped_round", "moshpit_set_tuning", "moshpit_copy_probe", "moshpit_check_bf16_rounding", "moshpit_sync", "moshpit_last_error",
 ]
 
 
@@ -84,6 +84,7 @@ def load_library() -> ctypes.CDLL:
     lib.moshpit_grouped_round.argtypes = [vp, vp, i64, i32, vp]
     lib.moshpit_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32, i32]
     lib.moshpit_copy_probe.argtypes = [vp, vp, i64, vp]
+    lib.moshpit_check_bf16_rounding.argtypes = [vp, vp]
     lib.moshpit_sync.argtypes = [vp]
     lib.moshpit_last_error.argtypes = [vp]
     lib.moshpit_last_error.restype = ctypes.c_char_p
@@ -323,6 +324,19 @@ def copy_probe(dst, src, stream=None) -> None:
     rc = load_library().moshpit_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream)
     if rc != 0:
         raise MoshpitError(f"copy_probe failed ({rc})")
+
+
+def check_bf16_rounding(stream=None) -> int:
+    """Number of binary32 inputs (of all 2^32) on which the hardware bfloat16 rounding the
+    kernels use differs from its integer definition; waits for the result."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    out = ctypes.c_uint64(2**64 - 1)
+    rc = load_library().moshpit_check_bf16_rounding(stream.cuda_stream, ctypes.byref(out))
+    if rc != 0:
+        raise MoshpitError(f"check_bf16_rounding failed ({rc})")
+    return int(out.value)
 
 
 def dist_to_mean_static(X, out, stream=None) -> None:

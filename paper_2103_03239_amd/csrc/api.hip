@@ -893,6 +893,23 @@ int moshpit_copy_probe(void *dst_dev, const void *src_dev, int64_t nbytes, void 
                : MOSHPIT_EHIP;
 }
 
+int moshpit_check_bf16_rounding(void *hip_stream, uint64_t *mismatches_out_host)
+{
+    if (!mismatches_out_host) return MOSHPIT_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned long long *count = nullptr;
+    if (hipMalloc(reinterpret_cast<void **>(&count), sizeof(unsigned long long)) != hipSuccess) return MOSHPIT_EHIP;
+    unsigned long long host = 0;
+    bool ok = hipMemsetAsync(count, 0, sizeof(unsigned long long), stream) == hipSuccess;
+    ok = ok && launch_bf16_rounding_check(count, stream) == hipSuccess;
+    ok = ok && hipMemcpyAsync(&host, count, sizeof(host), hipMemcpyDeviceToHost, stream) == hipSuccess;
+    ok = ok && hipStreamSynchronize(stream) == hipSuccess;
+    (void)hipFree(count);
+    if (!ok) return MOSHPIT_EHIP;
+    *mismatches_out_host = host;
+    return MOSHPIT_OK;
+}
+
 const char *moshpit_last_error(moshpit_ctx *h) { return h ? h->err : g_create_err; }
 
 }  // extern "C"

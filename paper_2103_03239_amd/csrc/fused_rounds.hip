@@ -32,6 +32,7 @@
 // flags: rows bytes][tile offset of
 // the first row of every group per axis][pad][RN(1/k), k = 0..64][16 bytes of zeros][16 bytes
 // of write-only trash].
+#include "bf16_round.h"
 #include "moshpit_internal.h"
 
 namespace moshpit {
@@ -49,13 +50,6 @@ constexpr int kRcpBytes = 272;       // 65 reciprocals, padded to a multiple of 
 constexpr int kNormalOrZero = 0x168;  // v_cmp_class mask: -normal, -0, +0, +normal
 constexpr int kMinSeg = 128;          // fewest bytes of a row in a tile
 constexpr int kPrefetch = 8;          // 128-bit vectors per thread: 1024 * 8 * 16 B = 128 KiB of tile
-
-__device__ __forceinline__ uint32_t bf16_bits_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
 
 // Block barrier that orders LDS traffic only.  __syncthreads() also waits for
 // every outstanding global load and store of the wave (its fence covers global
@@ -127,8 +121,7 @@ template <> struct Cols<1, 4> {
     }
     static __device__ __forceinline__ void store(elem_t *p, const float (&f)[4])
     {
-        *reinterpret_cast<u32x2 *>(p) = u32x2{bf16_bits_rne(f[0]) | (bf16_bits_rne(f[1]) << 16),
-                                              bf16_bits_rne(f[2]) | (bf16_bits_rne(f[3]) << 16)};
+        *reinterpret_cast<u32x2 *>(p) = u32x2{bf16_pair(f[0], f[1]), bf16_pair(f[2], f[3])};
     }
 };
 template <> struct Cols<1, 2> {
@@ -140,7 +133,7 @@ template <> struct Cols<1, 2> {
     }
     static __device__ __forceinline__ void store(elem_t *p, const float (&f)[2])
     {
-        *reinterpret_cast<uint32_t *>(p) = bf16_bits_rne(f[0]) | (bf16_bits_rne(f[1]) << 16);
+        *reinterpret_cast<uint32_t *>(p) = bf16_pair(f[0], f[1]);
     }
 };
 template <> struct Cols<1, 1> {
@@ -151,7 +144,7 @@ template <> struct Cols<1, 1> {
     }
     static __device__ __forceinline__ void store(elem_t *p, const float (&f)[1])
     {
-        *p = static_cast<uint16_t>(bf16_bits_rne(f[0]));
+        *p = bf16_one(f[0]);
     }
 };
 
@@ -172,7 +165,7 @@ template <int DT> __device__ __forceinline__ u32x4 local_step(const u32x4 &x, co
         for (int e = 0; e < 4; ++e) {
             const float lo = __fmaf_rn(-gamma, __uint_as_float(g[e] << 16), __uint_as_float(x[e] << 16));
             const float hi = __fmaf_rn(-gamma, __uint_as_float(g[e] & 0xffff0000u), __uint_as_float(x[e] & 0xffff0000u));
-            out[e] = bf16_bits_rne(lo) | (bf16_bits_rne(hi) << 16);
+            out[e] = bf16_pair(lo, hi);
         }
         return out;
     }

@@ -18,6 +18,7 @@
 //
 // The participant bitmap of a group is built by the wave itself: lane j < M
 // reads alive[base + j*S] and a ballot gives a 64-bit mask (hence M <= 64).
+#include "bf16_round.h"
 #include "moshpit_internal.h"
 
 namespace moshpit {
@@ -28,13 +29,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxBlock = 256;          // threads per block: 64, 128 or 256
 constexpr int kLdsPerCu = 160 * 1024;   // gfx950: LDS bytes per compute unit
-
-__device__ __forceinline__ uint32_t bf16_bits_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // keep NaN a NaN
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
 
 // How VE elements of storage type DT travel as one memory access and widen to
 // binary32.
@@ -76,7 +70,7 @@ template <> struct Vec<1, 8> {
     {
         uint32_t w[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) w[k] = bf16_bits_rne(f[2 * k]) | (bf16_bits_rne(f[2 * k + 1]) << 16);
+        for (int k = 0; k < 4; ++k) w[k] = bf16_pair(f[2 * k], f[2 * k + 1]);
         return mem_t{w[0], w[1], w[2], w[3]};
     }
 };
@@ -91,7 +85,7 @@ template <> struct Vec<1, 1> {
     }
     static __device__ __forceinline__ mem_t narrow(const float (&f)[NE])
     {
-        return static_cast<uint16_t>(bf16_bits_rne(f[0]));
+        return bf16_one(f[0]);
     }
 };
 

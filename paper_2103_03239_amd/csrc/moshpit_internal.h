@@ -171,4 +171,9 @@ hipError_t launch_fused_rounds(void *X, int dtype, const FusedPlan &plan, const 
 // Queue a plain 128-bit copy of nbytes (multiple of 16) from src to dst.
 hipError_t launch_copy_probe(void *dst, const void *src, int64_t nbytes, hipStream_t stream);
 
+// Queue the exhaustive comparison of the hardware binary32 -> bfloat16 conversion with
+// its integer definition: mismatches[0] (device, zeroed by the caller) counts the inputs,
+// out of all 2^32, on which the two differ.
+hipError_t launch_bf16_rounding_check(unsigned long long *mismatches, hipStream_t stream);
+
 }  // namespace moshpit

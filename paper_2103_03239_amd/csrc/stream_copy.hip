@@ -11,6 +11,7 @@
 // waves keep 16 loads in flight each).  The row copy reaches 6.3 TB/s with about a
 // million blocks that walk the work items; fewer, longer-running blocks are slower
 // (5.3 TB/s with 64 per compute unit).
+#include "bf16_round.h"
 #include "moshpit_internal.h"
 
 namespace moshpit {
@@ -155,6 +156,28 @@ hipError_t launch_refresh_copy(void *X, int dtype, int64_t N, int64_t P, int64_t
                    : launch_refresh_vecs<4, false>(s, g, base, row_bytes, valid, donor, returning, counts, stream);
     return vec ? launch_refresh_vecs<2, true>(s, g, base, row_bytes, valid, donor, returning, counts, stream)
                : launch_refresh_vecs<2, false>(s, g, base, row_bytes, valid, donor, returning, counts, stream);
+}
+
+namespace {
+// Thread i converts the two binary32 numbers with bit patterns 2i and 2i + 1 both ways.
+__global__ __launch_bounds__(256) void bf16_rounding_check_kernel(unsigned long long *mismatches)
+{
+    const uint64_t first = (static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x) * 2;
+    const float lo = __uint_as_float(static_cast<uint32_t>(first));
+    const float hi = __uint_as_float(static_cast<uint32_t>(first + 1));
+    const uint32_t hw = bf16_pair(lo, hi);
+    const uint32_t ref = (bf16_bits_reference(lo) & 0xffffu) | (bf16_bits_reference(hi) << 16);
+    const uint32_t one = bf16_one(lo);
+    const int bad = ((hw & 0xffffu) != (ref & 0xffffu) ? 1 : 0) + ((hw >> 16) != (ref >> 16) ? 1 : 0) +
+                    (one != (ref & 0xffffu) ? 1 : 0);
+    if (bad != 0) atomicAdd(mismatches, static_cast<unsigned long long>(bad));
+}
+}  // namespace
+
+hipError_t launch_bf16_rounding_check(unsigned long long *mismatches, hipStream_t stream)
+{
+    bf16_rounding_check_kernel<<<dim3(1u << 23), dim3(256), 0, stream>>>(mismatches);    // 2^31 pairs
+    return hipGetLastError();
 }
 
 hipError_t launch_copy_probe(void *dst, const void *src, int64_t nbytes, hipStream_t stream)

@@ -357,6 +357,13 @@ def test_full_size_full_state(cfg):
 
 
 
+def test_bf16_rounding_of_the_kernels_is_round_to_nearest_even_everywhere():
+    """The conversion instruction the kernels round bfloat16 states with, against its
+    integer definition, on all 2^32 binary32 inputs (the oracle's rounding is pinned to the
+    same definition on the CPU)."""
+    assert binding.check_bf16_rounding() == 0
+
+
 # --------------------------------------------------------------------------
 # fused multi-round passes
 # --------------------------------------------------------------------------
