@@ -335,7 +335,7 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     const int64_t nvec = aligned ? P / ve : 0;          // 128-bit part of every row
     const int64_t tail0 = nvec * ve;                    // first column of the element-wise part
 
-    // Defaults (measured on MI355X, see the sweep notes in the design document):
+    // Defaults (measured on MI355X over block sizes, rows in flight and resident waves):
     // one-wave blocks, each wave keeps about 16 KiB of row loads in flight
     // (rows per chunk x cols x 1 KiB) and 5-6 waves share a compute unit, i.e.
     // about 20-24 MiB in flight on the chip.  More than that and the HBM
