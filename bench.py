@@ -100,7 +100,7 @@ def time_oracle(orc, ref, w, threads, budget_s, step0=0):
 
 
 def measure(cfg: int, steps: int, warmup: int, cpu_cols: int, cpu_budget_s: float, tuning: str, row_pad: int,
-            full_oracle_curve: bool, extras: bool, copy_probe: bool):
+            full_oracle_curve: bool, extras: bool, copy_probe: bool, sgd_iteration: bool = True):
     """One workload: generate the state, run warm-up and timed steps, the fused variant,
     the distortion kernel, the parity sample and the CPU oracle.  Returns a dict of results."""
     import torch
@@ -242,7 +242,7 @@ def measure(cfg: int, steps: int, warmup: int, cpu_cols: int, cpu_budget_s: floa
     }
 
     if extras:
-        res.update(measure_extras(m, X, w, all_masks, row_stride, dev))
+        res.update(measure_extras(m, X, w, all_masks, row_stride, dev, sgd_iteration))
 
     if copy_probe:
         nbytes = min(w.N * w.P * s, 8 * 2 ** 30)
@@ -292,7 +292,7 @@ def measure(cfg: int, steps: int, warmup: int, cpu_cols: int, cpu_budget_s: floa
     return res
 
 
-def measure_extras(m, X, w, all_masks, row_stride, dev):
+def measure_extras(m, X, w, all_masks, row_stride, dev, sgd_iteration=True):
     """The widened entry points on the same state (random groups, chunk-index keys, the
     Moshpit SGD step, the refresh of returning peers)."""
     import torch
@@ -346,14 +346,15 @@ def measure_extras(m, X, w, all_masks, row_stride, dev):
     log(f"[bench] Moshpit SGD round: {sg_ms:.3f} ms per round, {out['sgd_round']['gbps']} GB/s")
     # a whole iteration of Moshpit SGD (local step + the workload's rounds): fused, the local step is
     # applied while the first pass loads its tiles; round by round it rides on the first round's kernel
-    from paper_2103_03239_amd import binding
-    sched = binding.Schedule(kind=w.kind, p=w.p, seed=w.mask_seed, down_rounds=w.down)
-    m.sgd_run(0, w.rounds, G, 1e-3, sched, flags=binding.RUN_FUSED)
-    it_fused = timed(lambda r: m.sgd_run((r + 1) * w.rounds, w.rounds, G, 1e-3, sched, flags=binding.RUN_FUSED), 3)
-    it_plain = timed(lambda r: m.sgd_run((r + 4) * w.rounds, w.rounds, G, 1e-3, sched), 3)
-    out["sgd_iteration"] = {"rounds": w.rounds, "ms_fused": round(it_fused, 4), "ms_round_by_round": round(it_plain, 4),
-                            "note": "theta - gamma*g for the peers present in the first round, then the rounds"}
-    log(f"[bench] Moshpit SGD iteration with {w.rounds} rounds: {it_fused:.3f} ms fused, {it_plain:.3f} ms round by round")
+    if sgd_iteration:
+        from paper_2103_03239_amd import binding
+        sched = binding.Schedule(kind=w.kind, p=w.p, seed=w.mask_seed, down_rounds=w.down)
+        m.sgd_run(0, w.rounds, G, 1e-3, sched, flags=binding.RUN_FUSED)
+        it_fused = timed(lambda r: m.sgd_run((r + 1) * w.rounds, w.rounds, G, 1e-3, sched, flags=binding.RUN_FUSED), 3)
+        it_plain = timed(lambda r: m.sgd_run((r + 4) * w.rounds, w.rounds, G, 1e-3, sched), 3)
+        out["sgd_iteration"] = {"rounds": w.rounds, "ms_fused": round(it_fused, 4), "ms_round_by_round": round(it_plain, 4),
+                                "note": "theta - gamma*g for the peers present in the first round, then the rounds"}
+        log(f"[bench] Moshpit SGD iteration with {w.rounds} rounds: {it_fused:.3f} ms fused, {it_plain:.3f} ms round by round")
     del G
 
     # returning peers copy an up-to-date peer's parameters (App. on a dynamic number of peers):
@@ -410,6 +411,9 @@ def main() -> int:
                     help="columns of the state the CPU oracle is timed on (0 = skip, -1 = auto)")
     ap.add_argument("--no-copy-probe", action="store_true")
     ap.add_argument("--no-fused", action="store_true", help="skip the widened entry points (random groups, SGD, refresh)")
+    ap.add_argument("--no-sgd-iteration", action="store_true",
+                    help="skip the Moshpit SGD iteration leg (its first pass is the fused kernel with a gradient read: "
+                         "leave it out when that kernel's plain passes are profiled)")
     ap.add_argument("--no-workloads", action="store_true", help="skip the short measurements of the other workloads")
     ap.add_argument("--tuning", type=str, default="", help="cols,unroll,nontemporal[,block,waves_per_cu] override for sweeps")
     ap.add_argument("--row-pad", type=int, default=0, help="extra elements between rows (row_stride = P + pad)")
@@ -427,7 +431,8 @@ def main() -> int:
         return 2
 
     head = measure(args.config, args.steps, args.warmup, args.cpu_cols, 10.0, args.tuning, args.row_pad,
-                   full_oracle_curve=(args.config == 2), extras=not args.no_fused, copy_probe=not args.no_copy_probe)
+                   full_oracle_curve=(args.config == 2), extras=not args.no_fused, copy_probe=not args.no_copy_probe,
+                   sgd_iteration=not args.no_sgd_iteration)
     w = head["w"]
     s = w.elem_size
 
