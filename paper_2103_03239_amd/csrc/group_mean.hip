@@ -18,88 +18,14 @@
 //
 // The participant bitmap of a group is built by the wave itself: lane j < M
 // reads alive[base + j*S] and a ballot gives a 64-bit mask (hence M <= 64).
-#include "bf16_round.h"
 #include "moshpit_internal.h"
+#include "row_vec.h"
 
 namespace moshpit {
 namespace {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int kMaxBlock = 256;          // threads per block: 64, 128 or 256
 constexpr int kLdsPerCu = 160 * 1024;   // gfx950: LDS bytes per compute unit
-
-// How VE elements of storage type DT travel as one memory access and widen to
-// binary32.
-template <int DT, int VE> struct Vec;
-
-template <> struct Vec<0, 4> {
-    typedef f32x4 mem_t;
-    static constexpr int NE = 4;
-    static __device__ __forceinline__ mem_t zero() { return mem_t{0.f, 0.f, 0.f, 0.f}; }
-    static __device__ __forceinline__ void widen(const mem_t &m, float (&f)[NE])
-    {
-        f[0] = m.x; f[1] = m.y; f[2] = m.z; f[3] = m.w;
-    }
-    static __device__ __forceinline__ mem_t narrow(const float (&f)[NE]) { return mem_t{f[0], f[1], f[2], f[3]}; }
-};
-
-template <> struct Vec<0, 1> {
-    typedef float mem_t;
-    static constexpr int NE = 1;
-    static __device__ __forceinline__ mem_t zero() { return 0.f; }
-    static __device__ __forceinline__ void widen(const mem_t &m, float (&f)[NE]) { f[0] = m; }
-    static __device__ __forceinline__ mem_t narrow(const float (&f)[NE]) { return f[0]; }
-};
-
-template <> struct Vec<1, 8> {
-    typedef u32x4 mem_t;
-    static constexpr int NE = 8;
-    static __device__ __forceinline__ mem_t zero() { return mem_t{0u, 0u, 0u, 0u}; }
-    static __device__ __forceinline__ void widen(const mem_t &m, float (&f)[NE])
-    {
-        const uint32_t w[4] = {m.x, m.y, m.z, m.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            f[2 * k] = __uint_as_float(w[k] << 16);             // even element: low half
-            f[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u); // odd element: high half
-        }
-    }
-    static __device__ __forceinline__ mem_t narrow(const float (&f)[NE])
-    {
-        uint32_t w[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) w[k] = bf16_pair(f[2 * k], f[2 * k + 1]);
-        return mem_t{w[0], w[1], w[2], w[3]};
-    }
-};
-
-template <> struct Vec<1, 1> {
-    typedef uint16_t mem_t;
-    static constexpr int NE = 1;
-    static __device__ __forceinline__ mem_t zero() { return 0; }
-    static __device__ __forceinline__ void widen(const mem_t &m, float (&f)[NE])
-    {
-        f[0] = __uint_as_float(static_cast<uint32_t>(m) << 16);
-    }
-    static __device__ __forceinline__ mem_t narrow(const float (&f)[NE])
-    {
-        return bf16_one(f[0]);
-    }
-};
-
-template <bool NT, typename T> __device__ __forceinline__ T load_vec(const T *p)
-{
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-
-template <bool NT, typename T> __device__ __forceinline__ void store_vec(T *p, const T &v)
-{
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
 
 // X            state, byte pointer to element (row 0, first column of this launch)
 // row_bytes    distance between rows in bytes
@@ -271,7 +197,7 @@ hipError_t launch_one(char *X, int64_t row_bytes, int64_t nvec, const uint8_t *a
     if (waves_per_cu > 0 && waves_per_cu < 32) {
         int blocks_per_cu = waves_per_cu / (block / 64);
         if (blocks_per_cu < 1) blocks_per_cu = 1;
-        lds = static_cast<size_t>(kLdsPerCu / blocks_per_cu) / 512 * 512;
+        lds = lds_bytes_for_blocks_per_cu(blocks_per_cu);
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kernel), kLdsPerCu);
         if (e != hipSuccess) return e;
     }
@@ -374,17 +300,22 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
     }
     int wpc = tune.waves_per_cu;
     if (wpc <= 0) {
+        // Resident waves per compute unit (measured; the optimum is sharp: on 16 MiB rows in
+        // groups of 32, 4 waves give 6.1 TB/s, 3 give 5.8 and 5 give 5.9).  A wave keeps
+        // rows x cols KiB of loads in flight (twice that with the gradients of the SGD step).
         const int rows = geom.M < unroll ? geom.M : unroll;
         const int kib_per_wave = rows * cols * (block / 64) * (geom.grad != nullptr ? 2 : 1);
-        wpc = (dtype == 0 ? 80 : 96) / kib_per_wave * (block / 64);
-        // groups of up to 16 rows (16 KiB in flight per wave): 6 waves; 8 when the rows are
-        // shorter than 1 MiB or when every die streams its own part of the list; 7 for groups
-        // given as a peer list; 6 for the Moshpit SGD step (which also streams the gradients)
-        if (rows * cols == 16 && geom.M <= 16) {
-            if (geom.grad != nullptr) wpc = 6;
+        wpc = (dtype == 0 ? 64 : 80) / kib_per_wave * (block / 64);
+        // groups of up to 16 rows (16 KiB in flight per wave): 5 waves; 7 when the rows are
+        // shorter than 1 MiB, for groups given as a peer list and when every die streams its
+        // own part of the list; 5 for the Moshpit SGD step (which also streams the gradients)
+        if (rows == 16 && cols == 1 && geom.M <= 16) {
+            if (geom.grad != nullptr) wpc = 5;
             else if (geom.index != nullptr) wpc = 7;
-            else wpc = (order == 1 || row_bytes < (1 << 20)) ? 8 : 6;
+            else wpc = (order == 1 || row_bytes < (1 << 20)) ? 7 : 5;
         }
+        // groups of up to 4 rows with one vector per row and lane (4 KiB in flight per wave)
+        if (rows * cols <= 4) wpc = 21;
         if (wpc < 4) wpc = 4;
         if (wpc > 32) wpc = 32;
     }

@@ -18,6 +18,17 @@ namespace moshpit {
 hipError_t ensure_dynamic_lds(const void *kernel, int bytes);
 hipError_t current_compute_units(int *out);
 
+// Dynamic-LDS size that lets `blocks` blocks of a kernel that uses no other LDS share a
+// compute unit of gfx950 (and no more, when 128 / blocks is a whole number or nearly so):
+// the 160 KiB are handed out in 128 pieces of 1280 bytes (measured: 3 blocks of 52 KiB fit,
+// 3 of 53 KiB do not; 2 of 80 KiB and 4 of 40 KiB fit).
+inline size_t lds_bytes_for_blocks_per_cu(int blocks)
+{
+    constexpr size_t kLds = 160 * 1024, kPiece = 1280;
+    if (blocks < 1) blocks = 1;
+    return kLds / static_cast<size_t>(blocks) / kPiece * kPiece;
+}
+
 // 128-bit item of the device sort, compared as (hi, lo).
 struct SortItem {
     uint64_t hi, lo;

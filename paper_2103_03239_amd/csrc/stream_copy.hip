@@ -33,7 +33,7 @@ size_t throttle_lds(const CopyShape &s)
     if (s.waves_per_cu <= 0 || s.waves_per_cu >= 32) return 0;
     int blocks_per_cu = s.waves_per_cu / (s.block / 64);
     if (blocks_per_cu < 1) blocks_per_cu = 1;
-    return static_cast<size_t>(kLdsPerCu / blocks_per_cu) / 512 * 512;
+    return lds_bytes_for_blocks_per_cu(blocks_per_cu);
 }
 
 // Block b copies vectors [b * blockDim * VECS, (b + 1) * blockDim * VECS) of nvec.
