@@ -263,8 +263,8 @@ hipError_t launch_group_mean(void *X, int dtype, int64_t P, int64_t row_stride, 
 
     // Defaults (measured on MI355X over block sizes, rows in flight and resident waves):
     // one-wave blocks, each wave keeps about 16 KiB of row loads in flight
-    // (rows per chunk x cols x 1 KiB) and 5-6 waves share a compute unit, i.e.
-    // about 20-24 MiB in flight on the chip.  More than that and the HBM
+    // (rows per chunk x cols x 1 KiB) and 4-7 waves share a compute unit, i.e.
+    // about 16-28 MiB in flight on the chip.  More than that and the HBM
     // controllers see too many open pages; less and latency is not covered.
     int cols = tune.cols, unroll = tune.unroll;
     if (cols <= 0 || unroll <= 0 || geom.index != nullptr || geom.grad != nullptr) {
