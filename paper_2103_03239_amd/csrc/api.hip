@@ -286,9 +286,27 @@ int stage_refresh_masks(moshpit_ctx *h, const uint8_t *prev_host, const uint8_t 
     return stage_to_device(h, h->d_refresh_masks + h->N, cur_host, static_cast<size_t>(h->N));
 }
 
-int queue_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev)
+// Fraction of non-zero bytes of a host mask (sizes launches only).
+float present_fraction(const uint8_t *alive_host, int64_t N)
+{
+    if (!alive_host || N <= 0) return 1.f;
+    int64_t n = 0;
+    for (int64_t i = 0; i < N; ++i) n += alive_host[i] != 0 ? 1 : 0;
+    return static_cast<float>(n) / static_cast<float>(N);
+}
+
+// Expected fraction of peers that take part in a round of schedule s (nullptr: everybody).
+float present_fraction(const moshpit_schedule *s)
+{
+    if (!s || s->kind == MOSHPIT_SCHED_NONE) return 1.f;
+    if (s->kind == MOSHPIT_SCHED_EXPLICIT) return -1.f;
+    return static_cast<float>(1.0 - s->p);
+}
+
+int queue_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev, float present = -1.f)
 {
     RoundGeom geom{h->N, h->M, axis_stride(h, t)};
+    geom.present = present;
     HIP_TRY(h, launch_group_mean(h->X, h->dtype, h->P, h->row_stride, geom, alive_dev, h->tune, h->stream));
     return MOSHPIT_OK;
 }
@@ -402,10 +420,10 @@ int moshpit_round(moshpit_ctx *h, int64_t t, const uint8_t *alive_host)
     int rc = check_ready(h);
     if (rc != MOSHPIT_OK) return rc;
     if (t < 0) return fail(h, MOSHPIT_EINVAL, "round index must be >= 0");
-    if (!alive_host) return queue_round(h, t, nullptr);
+    if (!alive_host) return queue_round(h, t, nullptr, 1.f);
     rc = stage_to_device(h, h->d_round_mask, alive_host, static_cast<size_t>(h->N));
     if (rc != MOSHPIT_OK) return rc;
-    return queue_round(h, t, h->d_round_mask);
+    return queue_round(h, t, h->d_round_mask, present_fraction(alive_host, h->N));
 }
 
 int moshpit_round_dev(moshpit_ctx *h, int64_t t, const uint8_t *alive_dev)
@@ -484,7 +502,7 @@ int run_impl(moshpit_ctx *h, int64_t t0, int32_t rounds, const moshpit_schedule 
             geom.gamma = gamma;
             HIP_TRY(h, launch_group_mean(h->X, h->dtype, h->P, h->row_stride, geom, mask_r, h->tune, h->stream));
         } else {
-            rc = queue_round(h, t0 + r, mask_r);
+            rc = queue_round(h, t0 + r, mask_r, present_fraction(s));
             if (rc != MOSHPIT_OK) return rc;
         }
         if (round_ms_out_host) HIP_TRY(h, hipEventRecord(h->events[2 * pass + 1], h->stream));

@@ -71,6 +71,9 @@ struct RoundGeom {
     const char *grad = nullptr;
     int64_t grad_row_bytes = 0;
     float gamma = 0.f;
+    // Fraction of the peers expected to take part (sizes the launch only: a wave keeps one row
+    // load in flight per participant, so fuller groups want fewer resident waves); < 0 = unknown
+    float present = -1.f;
 };
 
 // Queue one averaging round on `stream`.  X: device, row-major, `P` valid
